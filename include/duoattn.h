@@ -1,0 +1,150 @@
+/*
+ * duoattn.h - C ABI of the MI355X (gfx950) DuoAttention deployment hot path.
+ *
+ * What the library computes (paper, Section 2.2 and Section 2.3):
+ *   - every KV head of a layer is either a RETRIEVAL head (full causal attention
+ *     over all cached tokens) or a STREAMING head (attention restricted to the
+ *     first `sink` tokens plus a window of `recent` tokens, a Lambda-shaped mask);
+ *   - each layer owns two KV caches: a dense full-length cache for its retrieval
+ *     heads and a constant-length cache (sink slots + ring buffer) for its
+ *     streaming heads, the latter evicting the oldest non-sink token on append;
+ *   - decoding attends one new query per sequence against both caches and writes
+ *     the heads side by side; chunked pre-filling does the same for a chunk of
+ *     queries, after which the chunk is appended (which prunes the streaming cache).
+ *
+ * Conventions
+ *   - All tensors are DEVICE pointers unless a comment says HOST.  Q/K/V/out are
+ *     bf16, row-major, contiguous: [batch, n_tokens, n_heads, head_dim].
+ *   - Query head h belongs to KV head h / (n_q_heads / n_kv_heads).
+ *   - Positions are 0-based token indices inside one sequence.  A streaming query
+ *     at position i sees key j iff j <= i and (j < sink or i - j < recent): the
+ *     window counts the query's own position.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; they never synchronise.  One handle must be driven from
+ *     one stream at a time.
+ *   - The caller owns Q/K/V/out/lse; the library owns the caches and its split-K
+ *     scratch, allocated in duo_cache_create - nothing is allocated by append,
+ *     prefill or decode (the paper pre-allocates the cache for the whole run,
+ *     Section 3.4).
+ *   - Every entry point returns a duo_status_t (0 = ok).  Arguments are validated
+ *     before anything is launched; on error nothing has been enqueued and the
+ *     handle is unchanged.  duo_last_error() gives a thread-local message.
+ */
+#ifndef DUOATTN_H
+#define DUOATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct duo_cache duo_cache_t; /* opaque; owns device memory */
+
+typedef enum {
+  DUO_OK = 0,
+  DUO_EINVAL = -1, /* bad argument (NULL pointer, unsupported shape, bad mask) */
+  DUO_ENOMEM = -2, /* device or host allocation failed */
+  DUO_ERANGE = -3, /* append would exceed max_seq, index out of range */
+  DUO_ESTATE = -4, /* call does not fit the handle's state or geometry */
+  DUO_EHIP = -5    /* a HIP runtime call failed; see duo_last_error() */
+} duo_status_t;
+
+typedef enum {
+  DUO_KV_BF16 = 0,    /* caches hold the bf16 rows unchanged */
+  DUO_KV_FP8_E4M3 = 1 /* caches hold OCP E4M3 codes + one fp32 scale per (token, KV head),
+                         K and V separately: scale = amax/448 (1 if the row is all zero),
+                         code = RNE-saturating(x / scale), x_hat = value(code) * scale.
+                         This stands in for the paper's 4-bit KV setting (Section 3.4,
+                         combination with quantization). */
+} duo_kv_dtype_t;
+
+typedef struct {
+  int32_t n_layers;              /* >= 1 */
+  int32_t batch;                 /* >= 1; sequences advance in lock-step */
+  int32_t n_q_heads;             /* multiple of n_kv_heads, group size <= 8 */
+  int32_t n_kv_heads;            /* >= 1 */
+  int32_t head_dim;              /* 64 or 128 */
+  int32_t sink;                  /* >= 0 attention-sink tokens kept by streaming heads */
+  int32_t recent;                /* >= 1 recent tokens kept by streaming heads */
+  int64_t max_seq;               /* capacity of the full cache per sequence, >= 1 */
+  int32_t kv_dtype;              /* duo_kv_dtype_t */
+  const uint8_t* retrieval_mask; /* HOST, [n_layers][n_kv_heads], 1 = retrieval; copied */
+  float softmax_scale;           /* 0 -> 1/sqrt(head_dim) */
+} duo_config_t;
+
+/* Per-call restatement of the head classes and window geometry.  The ring
+ * geometry is fixed when the cache is created, so these must agree with the
+ * handle (DUO_ESTATE otherwise).  Passing NULL for the struct, or NULL for
+ * head_mask, means "use the handle's". */
+typedef struct {
+  const uint8_t* head_mask; /* HOST, [n_kv_heads] of this layer, 1 = retrieval */
+  int32_t sink;
+  int32_t recent;
+} duo_call_params_t;
+
+/* Allocate both caches of every layer (Section 2.3, Decoding: two KV caches per
+ * layer) and the split-K scratch.  DUO_EINVAL for unsupported shapes, DUO_ENOMEM
+ * if the device cannot hold the caches. */
+int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out);
+int duo_cache_destroy(duo_cache_t* cache);
+/* Forget all tokens of all layers (lengths -> 0).  Cache memory is not cleared. */
+int duo_cache_reset(duo_cache_t* cache);
+/* Tokens appended so far to `layer`, or a negative duo_status_t. */
+int64_t duo_cache_len(const duo_cache_t* cache, int layer);
+/* Bytes of device memory held by the caches (not counting scratch). */
+int64_t duo_cache_bytes(const duo_cache_t* cache);
+
+/* Append n_new tokens to `layer` at positions len .. len+n_new-1
+ * (Section 2.3: the retrieval cache stores all tokens; the streaming cache keeps
+ * only sinks and the most recent tokens, so an append overwrites the oldest
+ * non-sink entry).  k, v: [batch, n_new, n_kv_heads, head_dim] bf16.
+ * DUO_ERANGE if len + n_new > max_seq. */
+int duo_kv_append(duo_cache_t* cache, int layer, const void* k, const void* v,
+                  int n_new, const duo_call_params_t* params, void* stream);
+
+/* Chunked pre-filling attention (Section 2.3, Chunked Pre-filling; masks of
+ * Section 2.2).  q: [batch, n_new, n_q_heads, head_dim]; k, v: the chunk's own
+ * rows [batch, n_new, n_kv_heads, head_dim]; the cache supplies positions < len.
+ * Query r of the chunk sits at position len + r.  Retrieval heads see every key
+ * up to their own position; streaming heads see the Lambda mask exactly,
+ * whatever the chunk size.  The cache is NOT modified: call duo_kv_append with
+ * the same k, v afterwards.  out: bf16, shape of q.  lse: fp32
+ * [batch, n_q_heads, n_new] natural-log-sum-exp of the scaled scores, or NULL. */
+int duo_attn_prefill(duo_cache_t* cache, int layer, const void* q, const void* k,
+                     const void* v, int n_new, const duo_call_params_t* params,
+                     void* out, float* lse, void* stream);
+
+/* One decoding step (Section 2.3, Decoding).  q: [batch, 1, n_q_heads, head_dim].
+ * If k and v are NULL the new token has already been appended and the query sits
+ * at position len-1.  If both are given ([batch, 1, n_kv_heads, head_dim]) they
+ * are the new token's rows, the query sits at position len, and the result is
+ * that of append-then-attend, but the cache is left untouched.
+ * out: bf16 [batch, 1, n_q_heads, head_dim]; lse: fp32 [batch, n_q_heads] or NULL.
+ * DUO_ESTATE if the cache is empty and no k, v are given. */
+int duo_attn_decode(duo_cache_t* cache, int layer, const void* q, const void* k,
+                    const void* v, const duo_call_params_t* params, void* out,
+                    float* lse, void* stream);
+
+/* Test hook: the tokens one (layer, sequence, KV head) cache currently holds, in
+ * ascending position order.  k_out/v_out: device buffers of capacity
+ * `capacity` rows, each row head_dim bf16 (DUO_KV_BF16) or head_dim bytes
+ * (DUO_KV_FP8_E4M3); kscale_out/vscale_out: fp32 [capacity], fp8 mode only (may
+ * be NULL otherwise); positions_out: device int64 [capacity].  *count_out (HOST)
+ * receives the number of rows.  DUO_ERANGE if capacity is too small. */
+int duo_cache_export(duo_cache_t* cache, int layer, int batch_idx, int kv_head,
+                     void* k_out, void* v_out, float* kscale_out, float* vscale_out,
+                     int64_t* positions_out, int64_t capacity, int64_t* count_out,
+                     void* stream);
+
+/* Tuning knob: number of key splits per retrieval head in decode (0 = automatic).
+ * Results do not depend on it beyond floating-point rounding. */
+int duo_set_decode_splits(duo_cache_t* cache, int splits);
+
+/* Thread-local description of the last error returned on this thread. */
+const char* duo_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DUOATTN_H */

@@ -1,0 +1,326 @@
+// Host side of libduoattn: handle management, argument validation, launches.
+// The C ABI is documented in include/duoattn.h.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "duo_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+  return fail(DUO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+struct Layer {
+  duo::LayerView view;
+  std::vector<uint8_t> mask;  // host copy, [n_kv_heads]
+  int64_t len = 0;
+};
+
+}  // namespace
+
+struct duo_cache {
+  duo_config_t cfg;
+  std::vector<Layer> layers;
+  std::vector<void*> allocations;  // every device pointer owned by the handle
+  float* part_o = nullptr;
+  float* part_ml = nullptr;
+  int max_splits = 0;
+  int user_splits = 0;
+  int64_t cache_bytes = 0;
+};
+
+namespace {
+
+constexpr int kMaxSplits = 256;
+
+hipError_t dev_alloc(duo_cache* c, void** p, size_t bytes) {
+  if (bytes == 0) bytes = 256;
+  hipError_t e = hipMalloc(p, bytes);
+  if (e == hipSuccess) c->allocations.push_back(*p);
+  return e;
+}
+
+void release(duo_cache* c) {
+  for (void* p : c->allocations) (void)hipFree(p);
+  delete c;
+}
+
+int check_handle_layer(const duo_cache* c, int layer) {
+  if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers)
+    return fail(DUO_ERANGE, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  return DUO_OK;
+}
+
+int check_params(const duo_cache* c, int layer, const duo_call_params_t* p) {
+  if (!p) return DUO_OK;
+  if (p->sink != c->cfg.sink || p->recent != c->cfg.recent)
+    return fail(DUO_ESTATE, "call asks for sink=%d recent=%d but the cache was created with sink=%d recent=%d",
+                p->sink, p->recent, c->cfg.sink, c->cfg.recent);
+  if (p->head_mask) {
+    const Layer& L = c->layers[layer];
+    for (int h = 0; h < c->cfg.n_kv_heads; ++h) {
+      if ((p->head_mask[h] != 0) != (L.mask[h] != 0))
+        return fail(DUO_ESTATE, "head_mask[%d]=%d disagrees with the mask layer %d was created with",
+                    h, (int)p->head_mask[h], layer);
+    }
+  }
+  return DUO_OK;
+}
+
+// Splits per retrieval head: enough work items to fill the chip a few times
+// over while keeping at least kMinKeysPerSplit keys in each.
+int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
+  if (c->user_splits > 0) return c->user_splits < c->max_splits ? c->user_splits : c->max_splits;
+  const int64_t kMinKeysPerSplit = 256;
+  const int64_t target_items = 1024;
+  int64_t heads = (int64_t)L.view.n_ret * c->cfg.batch;
+  if (heads == 0) return 1;
+  int64_t s = (target_items + heads - 1) / heads;
+  int64_t by_len = keys / kMinKeysPerSplit;
+  if (s > by_len) s = by_len;
+  if (s > c->max_splits) s = c->max_splits;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* duo_last_error(void) { return g_err; }
+
+int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
+  if (!cfg || !out) return fail(DUO_EINVAL, "cfg and out must not be NULL");
+  *out = nullptr;
+  if (cfg->n_layers < 1) return fail(DUO_EINVAL, "n_layers must be >= 1 (got %d)", cfg->n_layers);
+  if (cfg->batch < 1) return fail(DUO_EINVAL, "batch must be >= 1 (got %d)", cfg->batch);
+  if (cfg->n_kv_heads < 1) return fail(DUO_EINVAL, "n_kv_heads must be >= 1 (got %d)", cfg->n_kv_heads);
+  if (cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads != 0)
+    return fail(DUO_EINVAL, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)",
+                cfg->n_q_heads, cfg->n_kv_heads);
+  int group = cfg->n_q_heads / cfg->n_kv_heads;
+  if (group != 1 && group != 2 && group != 4 && group != 8)
+    return fail(DUO_EINVAL, "query group size %d not supported (1, 2, 4 or 8)", group);
+  if (cfg->head_dim != 64 && cfg->head_dim != 128)
+    return fail(DUO_EINVAL, "head_dim %d not supported (64 or 128)", cfg->head_dim);
+  if (cfg->sink < 0) return fail(DUO_EINVAL, "sink must be >= 0 (got %d)", cfg->sink);
+  if (cfg->recent < 1) return fail(DUO_EINVAL, "recent must be >= 1 (got %d)", cfg->recent);
+  if ((int64_t)cfg->sink + cfg->recent > (1 << 20))
+    return fail(DUO_EINVAL, "sink + recent = %lld exceeds the supported streaming cache length 1048576",
+                (long long)cfg->sink + cfg->recent);
+  if (cfg->max_seq < 1) return fail(DUO_EINVAL, "max_seq must be >= 1 (got %lld)", (long long)cfg->max_seq);
+  if (cfg->max_seq > ((int64_t)1 << 31) - 1024)
+    return fail(DUO_EINVAL, "max_seq %lld exceeds the supported 2^31 - 1024", (long long)cfg->max_seq);
+  if (cfg->kv_dtype != DUO_KV_BF16 && cfg->kv_dtype != DUO_KV_FP8_E4M3)
+    return fail(DUO_EINVAL, "kv_dtype %d unknown", cfg->kv_dtype);
+  if (cfg->kv_dtype == DUO_KV_FP8_E4M3 && group == 8)
+    return fail(DUO_EINVAL, "query group size 8 is not supported with an fp8 cache");
+  if (!cfg->retrieval_mask) return fail(DUO_EINVAL, "retrieval_mask must not be NULL");
+  if (!(cfg->softmax_scale >= 0.0f) || std::isinf(cfg->softmax_scale))
+    return fail(DUO_EINVAL, "softmax_scale must be finite and >= 0");
+
+  duo_cache* c = new (std::nothrow) duo_cache();
+  if (!c) return fail(DUO_ENOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  c->cfg.retrieval_mask = nullptr;
+  c->layers.resize(cfg->n_layers);
+
+  const bool fp8 = cfg->kv_dtype == DUO_KV_FP8_E4M3;
+  const int row_bytes = fp8 ? cfg->head_dim : cfg->head_dim * 2;
+  const int64_t str_rows = (int64_t)cfg->sink + cfg->recent;
+  const float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  const int hkv = cfg->n_kv_heads, hq = cfg->n_q_heads;
+
+  // Per-layer tables (head classes and orders), one device array for all layers.
+  // Layout per layer: head_info[hkv] | ret_heads[hkv] | str_heads[hkv] | q_order[hq]
+  const int per_layer = 3 * hkv + hq;
+  std::vector<int32_t> tables((size_t)per_layer * cfg->n_layers, 0);
+  int32_t* d_tables = nullptr;
+  hipError_t e = dev_alloc(c, (void**)&d_tables, tables.size() * sizeof(int32_t));
+  if (e != hipSuccess) { release(c); return fail(e == hipErrorOutOfMemory ? DUO_ENOMEM : DUO_EHIP, "hipMalloc(tables): %s", hipGetErrorString(e)); }
+
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    Layer& L = c->layers[l];
+    L.mask.assign(cfg->retrieval_mask + (size_t)l * hkv, cfg->retrieval_mask + (size_t)(l + 1) * hkv);
+    int32_t* t = tables.data() + (size_t)l * per_layer;
+    int n_ret = 0, n_str = 0;
+    for (int h = 0; h < hkv; ++h) {
+      if (L.mask[h]) { t[h] = (int32_t)(duo::kRetrievalBit | (uint32_t)n_ret); t[hkv + n_ret] = h; ++n_ret; }
+      else { t[h] = n_str; t[2 * hkv + n_str] = h; ++n_str; }
+    }
+    int qi = 0;
+    for (int pass = 0; pass < 2; ++pass)
+      for (int h = 0; h < hkv; ++h)
+        if ((L.mask[h] != 0) == (pass == 0))
+          for (int g = 0; g < group; ++g) t[3 * hkv + qi++] = h * group + g;
+
+    duo::LayerView& v = L.view;
+    memset(&v, 0, sizeof(v));
+    v.head_info = (const uint32_t*)(d_tables + (size_t)l * per_layer);
+    v.ret_heads = d_tables + (size_t)l * per_layer + hkv;
+    v.str_heads = d_tables + (size_t)l * per_layer + 2 * hkv;
+    v.q_order = d_tables + (size_t)l * per_layer + 3 * hkv;
+    v.n_ret = n_ret; v.n_str = n_str;
+    v.batch = cfg->batch; v.n_q_heads = hq; v.n_kv_heads = hkv; v.group = group;
+    v.head_dim = cfg->head_dim; v.sink = cfg->sink; v.recent = cfg->recent;
+    v.row_bytes = row_bytes; v.fp8 = fp8 ? 1 : 0; v.max_seq = cfg->max_seq; v.scale = scale;
+
+    const size_t ret_bytes = (size_t)cfg->batch * n_ret * (size_t)cfg->max_seq * row_bytes;
+    const size_t str_bytes = (size_t)cfg->batch * n_str * (size_t)str_rows * row_bytes;
+    const size_t ret_sc = (size_t)cfg->batch * n_ret * (size_t)cfg->max_seq * sizeof(float);
+    const size_t str_sc = (size_t)cfg->batch * n_str * (size_t)str_rows * sizeof(float);
+    struct { void** p; size_t bytes; bool needed; } want[] = {
+        {(void**)&v.k_ret, ret_bytes, n_ret > 0}, {(void**)&v.v_ret, ret_bytes, n_ret > 0},
+        {(void**)&v.k_str, str_bytes, n_str > 0}, {(void**)&v.v_str, str_bytes, n_str > 0},
+        {(void**)&v.ks_ret, ret_sc, fp8 && n_ret > 0}, {(void**)&v.vs_ret, ret_sc, fp8 && n_ret > 0},
+        {(void**)&v.ks_str, str_sc, fp8 && n_str > 0}, {(void**)&v.vs_str, str_sc, fp8 && n_str > 0}};
+    for (auto& w : want) {
+      if (!w.needed) continue;
+      e = dev_alloc(c, w.p, w.bytes);
+      if (e != hipSuccess) {
+        release(c);
+        return fail(e == hipErrorOutOfMemory ? DUO_ENOMEM : DUO_EHIP,
+                    "hipMalloc of %zu bytes for layer %d failed: %s", w.bytes, l, hipGetErrorString(e));
+      }
+      c->cache_bytes += (int64_t)w.bytes;
+    }
+  }
+  e = hipMemcpy(d_tables, tables.data(), tables.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e != hipSuccess) { release(c); return fail_hip(e, "hipMemcpy(tables)"); }
+
+  c->max_splits = kMaxSplits;
+  e = dev_alloc(c, (void**)&c->part_o, (size_t)cfg->batch * hq * c->max_splits * cfg->head_dim * sizeof(float));
+  if (e == hipSuccess) e = dev_alloc(c, (void**)&c->part_ml, (size_t)cfg->batch * hq * c->max_splits * 2 * sizeof(float));
+  if (e != hipSuccess) { release(c); return fail(DUO_ENOMEM, "hipMalloc(split-K scratch): %s", hipGetErrorString(e)); }
+  *out = c;
+  return DUO_OK;
+}
+
+int duo_cache_destroy(duo_cache_t* c) {
+  if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
+  release(c);
+  return DUO_OK;
+}
+
+int duo_cache_reset(duo_cache_t* c) {
+  if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
+  for (auto& L : c->layers) L.len = 0;
+  return DUO_OK;
+}
+
+int64_t duo_cache_len(const duo_cache_t* c, int layer) {
+  int rc = check_handle_layer(c, layer);
+  if (rc != DUO_OK) return rc;
+  return c->layers[layer].len;
+}
+
+int64_t duo_cache_bytes(const duo_cache_t* c) {
+  if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
+  return c->cache_bytes;
+}
+
+int duo_set_decode_splits(duo_cache_t* c, int splits) {
+  if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
+  if (splits < 0 || splits > c->max_splits)
+    return fail(DUO_ERANGE, "splits %d outside [0, %d]", splits, c->max_splits);
+  c->user_splits = splits;
+  return DUO_OK;
+}
+
+int duo_kv_append(duo_cache_t* c, int layer, const void* k, const void* v, int n_new,
+                  const duo_call_params_t* params, void* stream) {
+  int rc = check_handle_layer(c, layer);
+  if (rc != DUO_OK) return rc;
+  if (!k || !v) return fail(DUO_EINVAL, "k and v must not be NULL");
+  if (n_new < 1) return fail(DUO_EINVAL, "n_new must be >= 1 (got %d)", n_new);
+  if ((rc = check_params(c, layer, params)) != DUO_OK) return rc;
+  Layer& L = c->layers[layer];
+  if (L.len + n_new > c->cfg.max_seq)
+    return fail(DUO_ERANGE, "append of %d tokens at length %lld exceeds max_seq %lld", n_new,
+                (long long)L.len, (long long)c->cfg.max_seq);
+  hipError_t e = duo::launch_append(L.view, k, v, L.len, n_new, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "append launch");
+  L.len += n_new;
+  return DUO_OK;
+}
+
+int duo_attn_prefill(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                     int n_new, const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  int rc = check_handle_layer(c, layer);
+  if (rc != DUO_OK) return rc;
+  if (!q || !k || !v || !out) return fail(DUO_EINVAL, "q, k, v and out must not be NULL");
+  if (n_new < 1) return fail(DUO_EINVAL, "n_new must be >= 1 (got %d)", n_new);
+  if ((rc = check_params(c, layer, params)) != DUO_OK) return rc;
+  Layer& L = c->layers[layer];
+  if (L.len + n_new > c->cfg.max_seq)
+    return fail(DUO_ERANGE, "chunk of %d tokens at length %lld exceeds max_seq %lld", n_new,
+                (long long)L.len, (long long)c->cfg.max_seq);
+  if (c->cfg.kv_dtype != DUO_KV_BF16)
+    return fail(DUO_EINVAL, "duo_attn_prefill supports bf16 caches only");
+  duo::PrefillArgs a;
+  a.lv = L.view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
+  hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "prefill launch");
+  return DUO_OK;
+}
+
+int duo_attn_decode(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                    const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  int rc = check_handle_layer(c, layer);
+  if (rc != DUO_OK) return rc;
+  if (!q || !out) return fail(DUO_EINVAL, "q and out must not be NULL");
+  if ((k == nullptr) != (v == nullptr)) return fail(DUO_EINVAL, "k and v must both be given or both be NULL");
+  if ((rc = check_params(c, layer, params)) != DUO_OK) return rc;
+  Layer& L = c->layers[layer];
+  if (!k && L.len == 0) return fail(DUO_ESTATE, "decode on an empty cache needs the new token's k and v");
+  if (k && L.len + 1 > c->cfg.max_seq)
+    return fail(DUO_ERANGE, "decode at length %lld exceeds max_seq %lld", (long long)L.len, (long long)c->cfg.max_seq);
+  if (k && c->cfg.kv_dtype != DUO_KV_BF16)
+    return fail(DUO_EINVAL, "decode with an un-appended token supports bf16 caches only");
+  duo::DecodeArgs a;
+  a.lv = L.view; a.q = q; a.k_new = k; a.v_new = v; a.out = out; a.lse = lse;
+  a.part_o = c->part_o; a.part_ml = c->part_ml; a.cache_len = L.len;
+  a.splits = choose_splits(c, L, L.len);
+  hipError_t e = duo::launch_decode(a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "decode launch");
+  return DUO_OK;
+}
+
+int duo_cache_export(duo_cache_t* c, int layer, int batch_idx, int kv_head, void* k_out, void* v_out,
+                     float* kscale_out, float* vscale_out, int64_t* positions_out, int64_t capacity,
+                     int64_t* count_out, void* stream) {
+  int rc = check_handle_layer(c, layer);
+  if (rc != DUO_OK) return rc;
+  if (batch_idx < 0 || batch_idx >= c->cfg.batch) return fail(DUO_ERANGE, "batch_idx %d outside [0, %d)", batch_idx, c->cfg.batch);
+  if (kv_head < 0 || kv_head >= c->cfg.n_kv_heads) return fail(DUO_ERANGE, "kv_head %d outside [0, %d)", kv_head, c->cfg.n_kv_heads);
+  if (!k_out || !v_out || !positions_out || !count_out) return fail(DUO_EINVAL, "k_out, v_out, positions_out and count_out must not be NULL");
+  const bool fp8 = c->cfg.kv_dtype == DUO_KV_FP8_E4M3;
+  if (fp8 && (!kscale_out || !vscale_out)) return fail(DUO_EINVAL, "scale outputs are required for an fp8 cache");
+  Layer& L = c->layers[layer];
+  int64_t count = L.mask[kv_head] ? L.len : duo::streaming_rows(L.len, c->cfg.sink, c->cfg.recent);
+  if (count > capacity) return fail(DUO_ERANGE, "export needs %lld rows but capacity is %lld", (long long)count, (long long)capacity);
+  *count_out = count;
+  if (count == 0) return DUO_OK;
+  hipError_t e = duo::launch_export(L.view, batch_idx, kv_head, L.len, k_out, v_out, kscale_out, vscale_out,
+                                    positions_out, count, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "export launch");
+  return DUO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Internal declarations shared by the host API and the HIP kernels of libduoattn.
+// Nothing here is part of the public C ABI (see include/duoattn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "duoattn.h"
+
+namespace duo {
+
+// Bit 31 of a head_info entry marks a retrieval KV head; the low bits hold the
+// head's slot inside its class's cache.
+constexpr uint32_t kRetrievalBit = 0x80000000u;
+
+// Device view of one layer's two caches.  Layouts (row = one token of one head):
+//   retrieval: [batch][n_ret][max_seq][row_bytes]            (+ scales [batch][n_ret][max_seq])
+//   streaming: [batch][n_str][sink + recent][row_bytes]      (+ scales [batch][n_str][sink+recent])
+// A streaming token at position p lives in slot p (p < sink) or
+// sink + (p - sink) % recent (ring buffer; the newest token overwrites the oldest).
+struct LayerView {
+  uint8_t* k_ret;
+  uint8_t* v_ret;
+  float* ks_ret;
+  float* vs_ret;
+  uint8_t* k_str;
+  uint8_t* v_str;
+  float* ks_str;
+  float* vs_str;
+  const uint32_t* head_info;  // [n_kv_heads]
+  const int32_t* ret_heads;   // [n_ret] KV head index of each retrieval slot
+  const int32_t* str_heads;   // [n_str]
+  const int32_t* q_order;     // [n_q_heads] query heads, retrieval groups first
+  int32_t n_ret, n_str;
+  int32_t batch, n_q_heads, n_kv_heads, group, head_dim;
+  int32_t sink, recent;
+  int32_t row_bytes;          // head_dim * 2 (bf16) or head_dim (fp8)
+  int32_t fp8;
+  int64_t max_seq;
+  float scale;                // softmax scale
+};
+
+struct DecodeArgs {
+  LayerView lv;
+  const void* q;       // [batch][n_q_heads][head_dim] bf16
+  const void* k_new;   // [batch][n_kv_heads][head_dim] bf16 or null
+  const void* v_new;
+  void* out;           // [batch][n_q_heads][head_dim] bf16
+  float* lse;          // [batch][n_q_heads] or null
+  float* part_o;       // [batch][n_q_heads][splits][head_dim]
+  float* part_ml;      // [batch][n_q_heads][splits][2]
+  int64_t cache_len;   // tokens held by the cache
+  int32_t splits;      // key splits per retrieval head
+};
+
+struct PrefillArgs {
+  LayerView lv;
+  const void* q;       // [batch][n][n_q_heads][head_dim]
+  const void* k;       // [batch][n][n_kv_heads][head_dim]
+  const void* v;
+  void* out;
+  float* lse;          // [batch][n_q_heads][n] or null
+  int64_t pos0;        // tokens in the cache = position of the chunk's first query
+  int32_t n;           // chunk length
+};
+
+hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int64_t pos0,
+                         int n_new, hipStream_t stream);
+hipError_t launch_export(const LayerView& lv, int batch_idx, int kv_head, int64_t len,
+                         void* k_out, void* v_out, float* ks_out, float* vs_out,
+                         int64_t* pos_out, int64_t count, hipStream_t stream);
+hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
+
+// Number of rows a streaming cache holds after `len` appends.
+__host__ __device__ inline int64_t streaming_rows(int64_t len, int sink, int recent) {
+  int64_t cap = (int64_t)sink + recent;
+  return len < cap ? len : cap;
+}
+
+}  // namespace duo

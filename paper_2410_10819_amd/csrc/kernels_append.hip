@@ -1,0 +1,192 @@
+// KV-cache append and export kernels.
+//
+// Append (paper, Section 2.3, Decoding / Chunked Pre-filling): a retrieval head
+// stores every token, so a new row goes to its position in the dense cache; a
+// streaming head keeps only the sink tokens and the most recent `recent` tokens,
+// so a new row at position p goes to slot p (p < sink) or to ring slot
+// sink + (p - sink) % recent, overwriting the oldest non-sink token.  When one
+// call appends more than `recent` tokens only the rows that survive are written,
+// so no two rows of a call ever target the same slot.
+#include "duo_internal.h"
+
+namespace duo {
+namespace {
+
+// fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448.
+__device__ inline uint32_t e4m3_encode(float x) {
+  uint32_t u = __float_as_uint(x);
+  uint32_t sign = (u >> 24) & 0x80u;
+  u &= 0x7FFFFFFFu;
+  float a = __uint_as_float(u);
+  uint32_t code;
+  if (a >= 448.0f) {
+    code = 0x7Eu;
+  } else if (a < 0.015625f) {             // below the smallest normal 2^-6: grid step 2^-9
+    code = (uint32_t)rintf(a * 512.0f);   // 8 carries into the smallest normal
+  } else {
+    uint32_t r = u + 0x7FFFFu + ((u >> 20) & 1u);   // RNE to 3 mantissa bits
+    code = (r >> 20) - ((127u - 7u) << 3);
+  }
+  return code | sign;
+}
+
+__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// One 16-byte chunk (8 bf16 values) of one row per thread; the head_dim/8 threads
+// of a row sit in adjacent lanes.
+template <int D, bool FP8>
+__global__ __launch_bounds__(256) void append_kernel(LayerView lv, const uint4* __restrict__ k_in,
+                                                     const uint4* __restrict__ v_in, int64_t pos0,
+                                                     int n_new, int64_t total_rows) {
+  constexpr int LPR = D / 8;  // lanes per row
+  const int64_t row = (int64_t)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  const int sub = threadIdx.x % LPR;
+  const bool live = row < total_rows;
+  const int64_t r = live ? row : total_rows - 1;
+  // row index -> (batch, token, kv head)
+  const int h = (int)(r % lv.n_kv_heads);
+  const int64_t bt = r / lv.n_kv_heads;
+  const int t = (int)(bt % n_new);
+  const int b = (int)(bt / n_new);
+  const int64_t p = pos0 + t;
+  const uint32_t info = lv.head_info[h];
+  const bool retrieval = (info & kRetrievalBit) != 0;
+  const int slot_head = (int)(info & ~kRetrievalBit);
+
+  bool write = live;
+  int64_t dst_row;  // row index inside the class's cache
+  if (retrieval) {
+    dst_row = ((int64_t)b * lv.n_ret + slot_head) * lv.max_seq + p;
+  } else {
+    const int64_t cap = (int64_t)lv.sink + lv.recent;
+    int64_t slot;
+    if (p < lv.sink) {
+      slot = p;
+    } else {
+      slot = lv.sink + (p - lv.sink) % lv.recent;
+      // rows of this call that a later row of the same call would overwrite
+      if (p + lv.recent < pos0 + n_new) write = false;
+    }
+    dst_row = ((int64_t)b * lv.n_str + slot_head) * cap + slot;
+  }
+  const uint4 kc = k_in[r * LPR + sub];
+  const uint4 vc = v_in[r * LPR + sub];
+  if constexpr (!FP8) {
+    if (write) {
+      uint4* kd = (uint4*)(retrieval ? lv.k_ret : lv.k_str);
+      uint4* vd = (uint4*)(retrieval ? lv.v_ret : lv.v_str);
+      kd[dst_row * LPR + sub] = kc;
+      vd[dst_row * LPR + sub] = vc;
+    }
+  } else {
+    const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
+    const uint32_t vw[4] = {vc.x, vc.y, vc.z, vc.w};
+    float kf[8], vf[8];
+    float kmax = 0.f, vmax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      kf[2 * i] = bf16_lo(kw[i]); kf[2 * i + 1] = bf16_hi(kw[i]);
+      vf[2 * i] = bf16_lo(vw[i]); vf[2 * i + 1] = bf16_hi(vw[i]);
+      kmax = fmaxf(kmax, fmaxf(fabsf(kf[2 * i]), fabsf(kf[2 * i + 1])));
+      vmax = fmaxf(vmax, fmaxf(fabsf(vf[2 * i]), fabsf(vf[2 * i + 1])));
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) {
+      kmax = fmaxf(kmax, __shfl_xor(kmax, off));
+      vmax = fmaxf(vmax, __shfl_xor(vmax, off));
+    }
+    const float ks = kmax == 0.f ? 1.0f : kmax / 448.0f;
+    const float vs = vmax == 0.f ? 1.0f : vmax / 448.0f;
+    uint32_t kq[2] = {0, 0}, vq[2] = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      kq[i / 4] |= e4m3_encode(kf[i] / ks) << (8 * (i % 4));
+      vq[i / 4] |= e4m3_encode(vf[i] / vs) << (8 * (i % 4));
+    }
+    if (write) {
+      uint2* kd = (uint2*)(retrieval ? lv.k_ret : lv.k_str);
+      uint2* vd = (uint2*)(retrieval ? lv.v_ret : lv.v_str);
+      kd[dst_row * LPR + sub] = make_uint2(kq[0], kq[1]);
+      vd[dst_row * LPR + sub] = make_uint2(vq[0], vq[1]);
+      if (sub == 0) {
+        (retrieval ? lv.ks_ret : lv.ks_str)[dst_row] = ks;
+        (retrieval ? lv.vs_ret : lv.vs_str)[dst_row] = vs;
+      }
+    }
+  }
+}
+
+// Copy the rows a head currently holds, in ascending position order.
+__global__ __launch_bounds__(256) void export_kernel(LayerView lv, int batch_idx, int kv_head, int64_t len,
+                                                     uint8_t* k_out, uint8_t* v_out, float* ks_out, float* vs_out,
+                                                     int64_t* pos_out, int64_t count) {
+  const int words_per_row = lv.row_bytes / 4;
+  const int rows_per_block = 256 / words_per_row;
+  const int64_t idx = (int64_t)blockIdx.x * rows_per_block + threadIdx.x / words_per_row;
+  const int w = threadIdx.x % words_per_row;
+  if (threadIdx.x / words_per_row >= rows_per_block || idx >= count) return;
+  const uint32_t info = lv.head_info[kv_head];
+  const bool retrieval = (info & kRetrievalBit) != 0;
+  const int slot_head = (int)(info & ~kRetrievalBit);
+  int64_t p, src_row;
+  if (retrieval) {
+    p = idx;
+    src_row = ((int64_t)batch_idx * lv.n_ret + slot_head) * lv.max_seq + p;
+  } else {
+    const int64_t cap = (int64_t)lv.sink + lv.recent;
+    const int64_t n_sink = len < lv.sink ? len : lv.sink;
+    if (idx < n_sink) {
+      p = idx;
+    } else {
+      const int64_t first = (len - lv.recent > lv.sink) ? len - lv.recent : lv.sink;
+      p = first + (idx - n_sink);
+    }
+    const int64_t slot = p < lv.sink ? p : lv.sink + (p - lv.sink) % lv.recent;
+    src_row = ((int64_t)batch_idx * lv.n_str + slot_head) * cap + slot;
+  }
+  const uint32_t* ks = (const uint32_t*)(retrieval ? lv.k_ret : lv.k_str);
+  const uint32_t* vs = (const uint32_t*)(retrieval ? lv.v_ret : lv.v_str);
+  ((uint32_t*)k_out)[idx * words_per_row + w] = ks[src_row * words_per_row + w];
+  ((uint32_t*)v_out)[idx * words_per_row + w] = vs[src_row * words_per_row + w];
+  if (w == 0) {
+    pos_out[idx] = p;
+    if (lv.fp8) {
+      ks_out[idx] = (retrieval ? lv.ks_ret : lv.ks_str)[src_row];
+      vs_out[idx] = (retrieval ? lv.vs_ret : lv.vs_str)[src_row];
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int64_t pos0, int n_new,
+                         hipStream_t stream) {
+  const int64_t total_rows = (int64_t)lv.batch * n_new * lv.n_kv_heads;
+  const int lpr = lv.head_dim / 8;
+  const int rows_per_block = 256 / lpr;
+  const int64_t blocks = (total_rows + rows_per_block - 1) / rows_per_block;
+  dim3 grid((unsigned)blocks), block(256);
+  const uint4* kk = (const uint4*)k;
+  const uint4* vv = (const uint4*)v;
+  if (lv.head_dim == 128) {
+    if (lv.fp8) append_kernel<128, true><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
+    else append_kernel<128, false><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
+  } else {
+    if (lv.fp8) append_kernel<64, true><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
+    else append_kernel<64, false><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_export(const LayerView& lv, int batch_idx, int kv_head, int64_t len, void* k_out, void* v_out,
+                         float* ks_out, float* vs_out, int64_t* pos_out, int64_t count, hipStream_t stream) {
+  const int words_per_row = lv.row_bytes / 4;
+  const int rows_per_block = 256 / words_per_row;
+  const int64_t blocks = (count + rows_per_block - 1) / rows_per_block;
+  export_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(lv, batch_idx, kv_head, len, (uint8_t*)k_out,
+                                                                   (uint8_t*)v_out, ks_out, vs_out, pos_out, count);
+  return hipGetLastError();
+}
+
+}  // namespace duo

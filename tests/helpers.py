@@ -1,0 +1,114 @@
+"""Shared helpers of the GPU parity tests: input staging and the scenario runner."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from paper_2410_10819_amd import synth
+
+ATOL_MAX = 2e-2     # max-abs bound on bf16 attention outputs vs the float64 oracle
+ATOL_MEAN = 2e-3    # mean-abs bound
+ATOL_LSE = 1e-3
+
+
+def to_dev(bits: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def from_dev_bits(t) -> np.ndarray:
+    import torch
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def from_dev_f64(t) -> np.ndarray:
+    return synth.bf16_bits_to_f64(from_dev_bits(t))
+
+
+def make_qkv(seed, batch, n_tok, hq, hkv, d, generator="counter", layer=0):
+    """bf16 bit patterns q [B,T,Hq,D], k, v [B,T,Hkv,D]."""
+    if generator == "counter":
+        q = synth.counter_bf16_batch(seed, layer, synth.TENSOR_Q, batch, 0, n_tok, hq, d)
+        k = synth.counter_bf16_batch(seed, layer, synth.TENSOR_K, batch, 0, n_tok, hkv, d)
+        v = synth.counter_bf16_batch(seed, layer, synth.TENSOR_V, batch, 0, n_tok, hkv, d)
+    else:
+        rng = np.random.default_rng(seed)
+        q = synth.randn_bf16(rng, (batch, n_tok, hq, d))
+        k = synth.randn_bf16(rng, (batch, n_tok, hkv, d))
+        v = synth.randn_bf16(rng, (batch, n_tok, hkv, d))
+    return q, k, v
+
+
+def assert_close(got_f64, want_f64, what=""):
+    diff = np.abs(got_f64 - want_f64)
+    assert np.isfinite(got_f64).all(), "%s: non-finite output" % what
+    assert diff.max() <= ATOL_MAX, "%s: max-abs %.4g > %.4g" % (what, diff.max(), ATOL_MAX)
+    assert diff.mean() <= ATOL_MEAN, "%s: mean-abs %.4g > %.4g" % (what, diff.mean(), ATOL_MEAN)
+    return diff.max(), diff.mean()
+
+
+def oracle_kv(k_bits, v_bits, fp8):
+    """float64 K/V history the oracle attends over (after the fp8 codec if enabled)."""
+    k = synth.bf16_bits_to_f64(k_bits)
+    v = synth.bf16_bits_to_f64(v_bits)
+    if fp8:
+        kc, ks = oracle.quantize_rows(k.astype(np.float32))
+        vc, vs = oracle.quantize_rows(v.astype(np.float32))
+        k, v = oracle.dequantize_rows(kc, ks), oracle.dequantize_rows(vc, vs)
+    return k, v
+
+
+def run_scenario(duo, cfg, q_bits, k_bits, v_bits, chunks, n_decode, fused_decode=False, want_lse=True,
+                 pass_params=False):
+    """Drive the library: prefill+append per chunk, then n_decode decode steps.
+
+    cfg: dict(batch, hq, hkv, d, sink, recent, mask [hkv], max_seq, kv_dtype, scale)
+    Returns (out_bits [B,T,Hq,D], lse [B,Hq,T], handle) with T = sum(chunks) + n_decode.
+    """
+    import torch
+    b, hq, hkv, d = cfg["batch"], cfg["hq"], cfg["hkv"], cfg["d"]
+    total = sum(chunks) + n_decode
+    assert q_bits.shape == (b, total, hq, d)
+    handle = duo.duo_cache_create(1, b, hq, hkv, d, cfg["sink"], cfg["recent"], cfg["max_seq"],
+                                  np.asarray(cfg["mask"], dtype=np.uint8)[None], cfg.get("kv_dtype", 0),
+                                  cfg.get("scale", 0.0))
+    params = (np.asarray(cfg["mask"], dtype=np.uint8), cfg["sink"], cfg["recent"]) if pass_params else None
+    out = np.zeros((b, total, hq, d), dtype=np.uint16)
+    lse = np.zeros((b, hq, total), dtype=np.float64)
+    pos = 0
+    for n in chunks:
+        qd, kd, vd = (to_dev(x[:, pos:pos + n]) for x in (q_bits, k_bits, v_bits))
+        od = torch.empty((b, n, hq, d), dtype=torch.bfloat16, device="cuda")
+        ld = torch.empty((b, hq, n), dtype=torch.float32, device="cuda") if want_lse else None
+        duo.duo_attn_prefill(handle, 0, qd, kd, vd, n, od, lse=ld, params=params)
+        duo.duo_kv_append(handle, 0, kd, vd, n, params=params)
+        torch.cuda.synchronize()
+        out[:, pos:pos + n] = from_dev_bits(od)
+        if want_lse:
+            lse[:, :, pos:pos + n] = ld.cpu().numpy()
+        pos += n
+        assert duo.duo_cache_len(handle, 0) == pos
+    for _ in range(n_decode):
+        qd, kd, vd = (to_dev(x[:, pos:pos + 1]) for x in (q_bits, k_bits, v_bits))
+        od = torch.empty((b, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+        ld = torch.empty((b, hq), dtype=torch.float32, device="cuda") if want_lse else None
+        if fused_decode:
+            duo.duo_attn_decode(handle, 0, qd, od, k=kd, v=vd, lse=ld, params=params)
+            duo.duo_kv_append(handle, 0, kd, vd, 1, params=params)
+        else:
+            duo.duo_kv_append(handle, 0, kd, vd, 1, params=params)
+            duo.duo_attn_decode(handle, 0, qd, od, lse=ld, params=params)
+        torch.cuda.synchronize()
+        out[:, pos] = from_dev_bits(od)[:, 0]
+        if want_lse:
+            lse[:, :, pos] = ld.cpu().numpy()
+        pos += 1
+    return out, lse, handle
+
+
+def oracle_rows(cfg, q_bits, k_bits, v_bits, positions, batch_idx=0):
+    """Oracle output/lse of the given positions of one sequence: (o [n,Hq,D], lse [Hq,n])."""
+    kf, vf = oracle_kv(k_bits[batch_idx], v_bits[batch_idx], cfg.get("kv_dtype", 0) == 1)
+    qf = synth.bf16_bits_to_f64(q_bits[batch_idx][np.asarray(positions)])
+    scale = cfg.get("scale", 0.0) or None
+    return oracle.attention_rows(qf, kf, vf, positions, cfg["mask"], cfg["sink"], cfg["recent"], scale)

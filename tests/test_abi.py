@@ -1,0 +1,83 @@
+"""The C-ABI library loads, exports every declared symbol, and validates arguments
+before touching the device (CPU only; no compute calls)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_10819_amd import binding as duo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(duo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = duo.load()
+    names = _declared("duoattn.h")
+    assert {"duo_kv_append", "duo_attn_prefill", "duo_attn_decode", "duo_cache_create"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    synth_lib = duo.load_synth()
+    for name in _declared("duo_synth.h"):
+        assert hasattr(synth_lib, name), name
+
+
+def test_binding_offers_the_same_names():
+    for name in _declared("duoattn.h") + _declared("duo_synth.h"):
+        if name == "duo_last_error":
+            continue
+        assert callable(getattr(duo, name)), name
+
+
+GOOD = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=8, head_dim=64, sink=16, recent=256, max_seq=4096)
+
+
+@pytest.mark.parametrize("change,fragment", [
+    (dict(n_layers=0), "n_layers"),
+    (dict(batch=0), "batch"),
+    (dict(n_kv_heads=0), "n_kv_heads"),
+    (dict(n_q_heads=12), "multiple"),
+    (dict(n_q_heads=24), "group size"),
+    (dict(head_dim=96), "head_dim"),
+    (dict(sink=-1), "sink"),
+    (dict(recent=0), "recent"),
+    (dict(max_seq=0), "max_seq"),
+    (dict(max_seq=2 ** 31), "max_seq"),
+    (dict(kv_dtype=7), "kv_dtype"),
+    (dict(softmax_scale=-1.0), "softmax_scale"),
+    (dict(n_q_heads=64, kv_dtype=1), "fp8"),
+])
+def test_create_rejects_bad_configs_before_allocating(change, fragment):
+    kw = dict(GOOD)
+    kw.update(change)
+    mask = np.ones((max(kw["n_layers"], 1), max(kw["n_kv_heads"], 1)), dtype=np.uint8)
+    if kw["n_layers"] < 1 or kw["n_kv_heads"] < 1:
+        mask = None
+    with pytest.raises((duo.DuoError, ValueError)) as exc:
+        duo.duo_cache_create(retrieval_mask=mask if mask is not None else np.zeros(0, np.uint8), **kw)
+    if isinstance(exc.value, duo.DuoError):
+        assert exc.value.status == duo.DUO_EINVAL
+        assert fragment in exc.value.message
+
+
+def test_null_arguments_are_reported_not_dereferenced():
+    lib = duo.load()
+    assert lib.duo_cache_create(None, None) == duo.DUO_EINVAL
+    assert b"NULL" in lib.duo_last_error()
+    assert lib.duo_cache_destroy(None) == duo.DUO_EINVAL
+    assert lib.duo_cache_len(None, 0) == duo.DUO_EINVAL
+    assert lib.duo_kv_append(None, 0, None, None, 1, None, None) == duo.DUO_EINVAL
+    assert lib.duo_attn_decode(None, 0, None, None, None, None, None, None, None) == duo.DUO_EINVAL
+    assert lib.duo_attn_prefill(None, 0, None, None, None, 1, None, None, None, None) == duo.DUO_EINVAL
+    cfg = duo.duo_config_t(**GOOD)
+    cfg.retrieval_mask = None
+    handle = ctypes.c_void_p()
+    assert lib.duo_cache_create(ctypes.byref(cfg), ctypes.byref(handle)) == duo.DUO_EINVAL
+    assert b"retrieval_mask" in lib.duo_last_error()

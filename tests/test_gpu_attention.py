@@ -1,0 +1,180 @@
+"""duo_attn_prefill / duo_attn_decode against the float64 oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2410_10819_amd import binding as duo
+from paper_2410_10819_amd import synth
+from helpers import (ATOL_LSE, assert_close, make_qkv, oracle_rows, run_scenario, to_dev, from_dev_f64)
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_all(cfg, q, k, v, out_bits, lse, positions=None):
+    total = q.shape[1]
+    positions = np.arange(total) if positions is None else np.asarray(positions)
+    worst = (0.0, 0.0)
+    for b in range(cfg["batch"]):
+        want_o, want_lse = oracle_rows(cfg, q, k, v, positions, b)
+        got = synth.bf16_bits_to_f64(out_bits[b][positions])
+        worst = max(worst, assert_close(got, want_o, "batch %d" % b))
+        if lse is not None:
+            assert np.abs(lse[b][:, positions] - want_lse).max() <= ATOL_LSE
+    return worst
+
+
+# configuration 1 of the benchmark list: 8 MHA heads, head_dim 64, 2048 prefill + 64 decode,
+# sink 16, recent 256, 4 of 8 heads retrieval.
+def _config1():
+    mask = synth.retrieval_mask(0, 1, 8, 0.5)[0]
+    return dict(batch=1, hq=8, hkv=8, d=64, sink=16, recent=256, mask=mask, max_seq=2048 + 64)
+
+
+@pytest.mark.parametrize("chunks", [[2048], [256] * 8])
+def test_config1_full_tensor_parity(chunks):
+    cfg = _config1()
+    q, k, v = make_qkv(1, 1, 2048 + 64, 8, 8, 64)
+    out, lse, handle = run_scenario(duo, cfg, q, k, v, chunks, 64)
+    try:
+        _check_all(cfg, q, k, v, out, lse)
+    finally:
+        duo.duo_cache_destroy(handle)
+
+
+def test_config1_numpy_rng_inputs_and_fused_decode():
+    cfg = _config1()
+    q, k, v = make_qkv(5, 1, 1024 + 48, 8, 8, 64, generator="numpy")
+    cfg["max_seq"] = 1024 + 48
+    out, lse, handle = run_scenario(duo, cfg, q, k, v, [1024], 48, fused_decode=True, pass_params=True)
+    try:
+        _check_all(cfg, q, k, v, out, lse)
+    finally:
+        duo.duo_cache_destroy(handle)
+
+
+@pytest.mark.parametrize("hq,hkv,d,sink,recent,chunks,n_decode,batch", [
+    (8, 2, 128, 4, 32, [300, 1, 77, 130], 20, 2),       # GQA 4, ragged chunks, batch 2
+    (4, 4, 128, 64, 256, [129, 513], 9, 1),             # deployment constants, tile tails
+    (16, 2, 64, 0, 5, [70, 70], 12, 1),                 # GQA 8, no sinks, tiny window
+    (4, 2, 64, 3, 1, [65], 6, 3),                       # window of one token
+    (2, 2, 128, 8, 1000, [100, 50], 5, 1),              # window longer than the sequence
+])
+def test_mixed_heads_ragged_shapes(hq, hkv, d, sink, recent, chunks, n_decode, batch):
+    total = sum(chunks) + n_decode
+    mask = np.array([(h % 2) for h in range(hkv)], dtype=np.uint8)
+    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=sink, recent=recent, mask=mask, max_seq=total)
+    q, k, v = make_qkv(hq * 100 + d, batch, total, hq, hkv, d)
+    out, lse, handle = run_scenario(duo, cfg, q, k, v, chunks, n_decode)
+    try:
+        _check_all(cfg, q, k, v, out, lse)
+    finally:
+        duo.duo_cache_destroy(handle)
+
+
+@pytest.mark.parametrize("mask_kind", ["all_retrieval", "all_streaming"])
+def test_single_class_layers(mask_kind):
+    hq, hkv, d, total = 4, 4, 64, 400
+    mask = np.full(hkv, 1 if mask_kind == "all_retrieval" else 0, dtype=np.uint8)
+    cfg = dict(batch=1, hq=hq, hkv=hkv, d=d, sink=4, recent=16, mask=mask, max_seq=total)
+    q, k, v = make_qkv(9, 1, total, hq, hkv, d)
+    out, lse, handle = run_scenario(duo, cfg, q, k, v, [150, 200], 50)
+    try:
+        _check_all(cfg, q, k, v, out, lse)
+    finally:
+        duo.duo_cache_destroy(handle)
+
+
+def test_decode_only_from_empty_cache_and_split_independence():
+    import torch
+    hq, hkv, d, total = 8, 2, 128, 1500
+    mask = np.array([1, 0], dtype=np.uint8)
+    cfg = dict(batch=1, hq=hq, hkv=hkv, d=d, sink=4, recent=64, mask=mask, max_seq=total)
+    q, k, v = make_qkv(21, 1, total, hq, hkv, d)
+    handle = duo.duo_cache_create(1, 1, hq, hkv, d, 4, 64, total, mask[None])
+    try:
+        # first tokens one by one (fused form on the empty cache), then a bulk append
+        outs = {}
+        for t in range(3):
+            qd, kd, vd = (to_dev(x[:, t:t + 1]) for x in (q, k, v))
+            od = torch.empty((1, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+            duo.duo_attn_decode(handle, 0, qd, od, k=kd, v=vd)
+            duo.duo_kv_append(handle, 0, kd, vd, 1)
+            outs[t] = from_dev_f64(od)[0, 0]
+        duo.duo_kv_append(handle, 0, to_dev(k[:, 3:total]), to_dev(v[:, 3:total]), total - 3)
+        qd = to_dev(q[:, total - 1:total])
+        results = []
+        for splits in (0, 1, 2, 7, 64):
+            duo.duo_set_decode_splits(handle, splits)
+            od = torch.empty((1, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+            ld = torch.empty((1, hq), dtype=torch.float32, device="cuda")
+            duo.duo_attn_decode(handle, 0, qd, od, lse=ld)
+            results.append((from_dev_f64(od)[0, 0], ld.cpu().numpy()[0]))
+        want_o, want_lse = oracle_rows(cfg, q, k, v, [0, 1, 2, total - 1])
+        for t in range(3):
+            assert_close(outs[t], want_o[t], "token %d" % t)
+        for got, got_lse in results:
+            assert_close(got, want_o[3], "last token")
+            assert np.abs(got_lse - want_lse[:, 3]).max() <= ATOL_LSE
+        # determinism: same call twice -> identical bits
+        od2 = torch.empty((1, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+        duo.duo_attn_decode(handle, 0, qd, od2)
+        od3 = torch.empty((1, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+        duo.duo_attn_decode(handle, 0, qd, od3)
+        assert torch.equal(od2, od3)
+    finally:
+        duo.duo_cache_destroy(handle)
+
+
+def test_one_hot_value_probe_on_device():
+    # Q = 0 -> uniform softmax; V one-hot at j* -> output 1/|Vis| or exactly 0 (mask edges)
+    import torch
+    hq = hkv = 2
+    d, sink, recent, total = 64, 16, 48, 200      # S + R = 64: power-of-two counts are exact in bf16
+    mask = np.array([1, 0], dtype=np.uint8)
+    cfg = dict(batch=1, hq=hq, hkv=hkv, d=d, sink=sink, recent=recent, mask=mask, max_seq=total)
+    q = np.zeros((1, total, hq, d), dtype=np.uint16)
+    k = make_qkv(2, 1, total, hq, hkv, d)[1]
+    for jstar in (0, 15, 16, 100, 151, 152):
+        v = np.zeros((1, total, hkv, d), dtype=np.uint16)
+        v[0, jstar, :, 0] = 0x3F80                # bf16 1.0
+        out, _, handle = run_scenario(duo, cfg, q, k, v, [128, 64], 8, want_lse=False)
+        duo.duo_cache_destroy(handle)
+        got = synth.bf16_bits_to_f64(out)[0, :, :, 0]
+        for i in range(total):
+            in_vis = jstar <= i and (jstar < sink or i - jstar < recent)
+            if not in_vis:
+                assert got[i, 1] == 0.0, (jstar, i)
+            else:
+                assert abs(got[i, 1] - 1.0 / min(i + 1, sink + recent)) <= 2.0 ** -8 / min(i + 1, 64)
+            if jstar > i:
+                assert got[i, 0] == 0.0
+            else:
+                assert abs(got[i, 0] - 1.0 / (i + 1)) <= 2.0 ** -8 / (i + 1)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(8, 2, 128), (4, 4, 64)])
+def test_fp8_cache_decode(hq, hkv, d):
+    import torch
+    total, n_decode = 700, 12
+    mask = np.array([(h + 1) % 2 for h in range(hkv)], dtype=np.uint8)
+    cfg = dict(batch=2, hq=hq, hkv=hkv, d=d, sink=8, recent=40, mask=mask, max_seq=total, kv_dtype=1)
+    q, k, v = make_qkv(31, 2, total, hq, hkv, d)
+    handle = duo.duo_cache_create(1, 2, hq, hkv, d, 8, 40, total, mask[None], duo.DUO_KV_FP8_E4M3)
+    try:
+        pos = total - n_decode
+        duo.duo_kv_append(handle, 0, to_dev(k[:, :pos]), to_dev(v[:, :pos]), pos)
+        got = np.zeros((2, n_decode, hq, d))
+        got_lse = np.zeros((2, hq, n_decode))
+        for t in range(n_decode):
+            duo.duo_kv_append(handle, 0, to_dev(k[:, pos + t:pos + t + 1]), to_dev(v[:, pos + t:pos + t + 1]), 1)
+            od = torch.empty((2, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+            ld = torch.empty((2, hq), dtype=torch.float32, device="cuda")
+            duo.duo_attn_decode(handle, 0, to_dev(q[:, pos + t:pos + t + 1]), od, lse=ld)
+            got[:, t] = from_dev_f64(od)[:, 0]
+            got_lse[:, :, t] = ld.cpu().numpy()
+        for b in range(2):
+            want_o, want_lse = oracle_rows(cfg, q, k, v, np.arange(pos, total), b)
+            assert_close(got[b], want_o, "fp8 batch %d" % b)
+            assert np.abs(got_lse[b] - want_lse).max() <= ATOL_LSE
+    finally:
+        duo.duo_cache_destroy(handle)
