@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the DuoAttention hot path on one MI355X.
+
+Default workload (the configuration the headline metric is quoted on): a
+Llama-2-7B-shaped MHA layer - 32 query/KV heads, head_dim 128, 25 % retrieval
+heads (seeded), 64 sink + 256 recent tokens, batch 1.  One "step" is one pass of
+the whole path: reset the cache, pre-fill 32 768 tokens in 4 096-token chunks
+(attention + append per chunk), then 256 decoding steps (append + attention).
+All inputs are synthetic bf16 N(0,1) tensors generated on the device before the
+timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+
+WORKLOADS = {
+    # name: (hq, hkv, d, ratio, sink, recent, prefill_tokens, chunk, decode_steps, batch, kv_dtype, append_only_fill)
+    "c1": dict(hq=8, hkv=8, d=64, ratio=0.5, sink=16, recent=256, prefill=2048, chunk=2048, decode=64, batch=1,
+               desc="toy MHA 8x64, prefill 2048 + 64 decode"),
+    "c2": dict(hq=32, hkv=32, d=128, ratio=0.25, sink=64, recent=256, prefill=32768, chunk=4096, decode=256, batch=1,
+               desc="Llama-2-7B-shaped MHA layer, 25% retrieval heads, sink 64, recent 256, "
+                    "prefill 32768 in 4096-token chunks + 256 decode steps, batch 1"),
+    "c3_prefill": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=32768, decode=0,
+                       batch=1, desc="Llama-3-8B-shaped GQA layer, 50% retrieval KV heads, prefill 131072 in "
+                                     "32768-token chunks, batch 1"),
+    "c3_decode_b1": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=0, decode=64,
+                         batch=1, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 1"),
+    "c3_decode_b4": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=0, decode=64,
+                         batch=4, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 4"),
+    "c3_decode_b16": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=0, decode=32,
+                          batch=16, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 16"),
+}
+
+
+def visible_pairs(pos0, n, sink, recent, retrieval):
+    """Number of unmasked (query, key) pairs of a chunk of n queries starting at position pos0."""
+    i = np.arange(pos0, pos0 + n, dtype=np.int64)
+    if retrieval:
+        return int((i + 1).sum())
+    return int(np.minimum(i + 1, sink + recent).sum())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_10819_amd import binding as duo
+    from paper_2410_10819_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    lib = duo.load()                      # raises if the HIP library is missing: no fallback
+    w = WORKLOADS[args.workload]
+    hq, hkv, d, B = w["hq"], w["hkv"], w["d"], w["batch"]
+    sink, recent = w["sink"], w["recent"]
+    n_prefill, chunk, n_decode = w["prefill"], w["chunk"], w["decode"]
+    group = hq // hkv
+    total = n_prefill + n_decode
+    mask = synth.retrieval_mask(args.seed, 1, hkv, w["ratio"])
+    n_ret = int(mask.sum())
+    n_str = hkv - n_ret
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- synthetic inputs, generated on the device (bit-identical to the CPU generator)
+    table = torch.from_numpy(synth.normal_table_bf16().view(np.int16)).cuda()
+
+    def fill(tensor_id, heads, n_pos):
+        t = torch.empty((B, n_pos, heads, d), dtype=torch.bfloat16, device="cuda")
+        for b in range(B):
+            duo.duo_synth_fill_bf16(t[b], table, synth.stream_key(args.seed, 0, tensor_id, b), 0, n_pos, heads, d)
+        return t
+
+    attn_prefill = chunk > 0
+    q_all = fill(synth.TENSOR_Q, hq, total) if attn_prefill else None
+    k_all = fill(synth.TENSOR_K, hkv, total)
+    v_all = fill(synth.TENSOR_V, hkv, total)
+    # decode-phase inputs as separate contiguous [B, 1, H, D] slices
+    if attn_prefill:
+        q_dec = [q_all[:, n_prefill + t:n_prefill + t + 1].contiguous() for t in range(n_decode)]
+    else:
+        qd = torch.empty((B, n_decode, hq, d), dtype=torch.bfloat16, device="cuda")
+        for b in range(B):
+            duo.duo_synth_fill_bf16(qd[b], table, synth.stream_key(args.seed, 0, synth.TENSOR_Q, b), n_prefill,
+                                    n_decode, hq, d)
+        q_dec = [qd[:, t:t + 1].contiguous() for t in range(n_decode)]
+    k_dec = [k_all[:, n_prefill + t:n_prefill + t + 1].contiguous() for t in range(n_decode)]
+    v_dec = [v_all[:, n_prefill + t:n_prefill + t + 1].contiguous() for t in range(n_decode)]
+    chunks = []
+    if attn_prefill:
+        for p in range(0, n_prefill, chunk):
+            n = min(chunk, n_prefill - p)
+            chunks.append((p, n, q_all[:, p:p + n].contiguous() if B > 1 else q_all[:, p:p + n],
+                           k_all[:, p:p + n].contiguous() if B > 1 else k_all[:, p:p + n],
+                           v_all[:, p:p + n].contiguous() if B > 1 else v_all[:, p:p + n]))
+    out_pre = torch.empty((B, max(chunk, 1), hq, d), dtype=torch.bfloat16, device="cuda")
+    out_dec = torch.empty((B, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+    handle = duo.duo_cache_create(1, B, hq, hkv, d, sink, recent, total, mask)
+    torch.cuda.synchronize()
+
+    # raw pointers so the timed loop is not dominated by Python-side tensor checks
+    P = lambda t: t.data_ptr()
+    chunk_ptrs = [(n, P(qc), P(kc), P(vc)) for (_, n, qc, kc, vc) in chunks]
+    dec_ptrs = [(P(q_dec[t]), P(k_dec[t]), P(v_dec[t])) for t in range(n_decode)]
+    p_out_pre, p_out_dec = P(out_pre), P(out_dec)
+    k_fill = k_all[:, :n_prefill] if B == 1 else k_all[:, :n_prefill].contiguous()
+    v_fill = v_all[:, :n_prefill] if B == 1 else v_all[:, :n_prefill].contiguous()
+
+    def check(rc):
+        if rc != 0:
+            raise duo.DuoError(rc, lib.duo_last_error().decode())
+
+    def prefill_phase():
+        if attn_prefill:
+            for n, pq, pk, pv in chunk_ptrs:
+                check(lib.duo_attn_prefill(handle, 0, pq, pk, pv, n, None, p_out_pre, None, stream))
+                check(lib.duo_kv_append(handle, 0, pk, pv, n, None, stream))
+        else:
+            check(lib.duo_kv_append(handle, 0, P(k_fill), P(v_fill), n_prefill, None, stream))
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    dec_events = [(ev(), ev()) for _ in range(n_decode)]
+
+    def decode_phase(timed):
+        for t, (pq, pk, pv) in enumerate(dec_ptrs):
+            check(lib.duo_kv_append(handle, 0, pk, pv, 1, None, stream))
+            if timed:
+                dec_events[t][0].record()
+            check(lib.duo_attn_decode(handle, 0, pq, None, None, None, p_out_dec, None, stream))
+            if timed:
+                dec_events[t][1].record()
+
+    pre_ms, dec_ms, dec_kernel_ms = [], [], []
+    e0, e1, e2 = ev(), ev(), ev()
+
+    def one_step(timed):
+        duo.duo_cache_reset(handle)
+        if timed:
+            e0.record()
+        prefill_phase()
+        if timed:
+            e1.record()
+        decode_phase(timed)
+        if timed:
+            e2.record()
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+        torch.cuda.synchronize()
+        pre_ms.append(e0.elapsed_time(e1))
+        dec_ms.append(e1.elapsed_time(e2))
+        if n_decode:
+            dec_kernel_ms.append(sum(a.elapsed_time(b) for a, b in dec_events) / n_decode)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ---- algorithmic work
+    row_bytes = 2 * d
+    dec_bytes = []
+    for t in range(n_decode):
+        n_ctx = n_prefill + t + 1
+        dec_bytes.append(B * (n_ret * 2 * n_ctx * row_bytes + n_str * 2 * min(n_ctx, sink + recent) * row_bytes
+                              + 2 * hq * d * 2))
+    avg_dec_bytes = float(np.mean(dec_bytes)) if dec_bytes else 0.0
+    flops = 0
+    for p, n, *_ in chunks:
+        pairs = group * B * (n_ret * visible_pairs(p, n, sink, recent, True)
+                             + n_str * visible_pairs(p, n, sink, recent, False))
+        flops += 4 * d * pairs
+    pre_t = float(np.mean(pre_ms)) * 1e-3
+    dec_t = float(np.mean(dec_ms)) * 1e-3
+    us_per_token = dec_t / n_decode * 1e6 if n_decode else None
+    dec_call_us = float(np.mean(dec_kernel_ms)) * 1e3 if dec_kernel_ms else None
+    dec_gbps = avg_dec_bytes / (dec_call_us * 1e-6) / 1e9 if dec_call_us else None
+    pre_tflops = flops / pre_t / 1e12 if attn_prefill and pre_t > 0 else None
+
+    roof_dec = None
+    if dec_gbps:
+        roof_dec = {"bound": "hbm", "achieved": round(dec_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(dec_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "kernel": "duo::decode_kernel", "bytes_per_launch": int(avg_dec_bytes),
+                    "avg_launch_us": round(dec_call_us, 2)}
+    roof_pre = None
+    if pre_tflops:
+        roof_pre = {"bound": "mfma", "achieved": round(pre_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "kernel": "duo::prefill_kernel", "flops_per_step": int(flops),
+                    "avg_chunk_ms": round(pre_t * 1e3 / max(len(chunks), 1), 3)}
+    dominant = roof_dec if (roof_pre is None or (roof_dec is not None and dec_t >= pre_t)) else roof_pre
+
+    # ---- the oracle on the host cores, bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline and n_decode:
+        import oracle
+        n_sample = 4 if n_prefill <= 40000 else 1
+        t_hist = n_prefill + n_sample
+        kh = synth.bf16_bits_to_f64(k_all[0, :t_hist].cpu().view(torch.int16).numpy().view(np.uint16))
+        vh = synth.bf16_bits_to_f64(v_all[0, :t_hist].cpu().view(torch.int16).numpy().view(np.uint16))
+        qh = [synth.bf16_bits_to_f64(q_dec[t][0, 0].cpu().view(torch.int16).numpy().view(np.uint16))
+              for t in range(n_sample)]
+        t0 = time.perf_counter()
+        for t in range(n_sample):
+            oracle.decode_step(qh[t], kh[:n_prefill + t + 1], vh[:n_prefill + t + 1], mask[0], sink, recent)
+        cpu_s = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = 1
+        cpu = {"value": round(cpu_s / n_sample * 1e6 * B, 1), "unit": "us/token", "cores": int(threads),
+               "kind": "oracle", "host_cores_available": len(os.sched_getaffinity(0)),
+               "sample": "%d decode tokens of sequence 0 at context %d (float64 numpy oracle), scaled by batch %d"
+                         % (n_sample, n_prefill, B)}
+
+    result = {
+        "metric": "decode_attn_us_per_token" if n_decode else "prefill_attn_tflops",
+        "value": round(us_per_token, 3) if n_decode else round(pre_tflops, 2),
+        "unit": "us/token" if n_decode else "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": False if n_decode else True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w["desc"], "name": args.workload, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": d,
+                   "retrieval_kv_heads": n_ret, "sink": sink, "recent": recent, "batch": B,
+                   "prefill_tokens": n_prefill, "chunk": chunk, "decode_steps": n_decode},
+        "decode_hbm_GBps": round(dec_gbps, 1) if dec_gbps else None,
+        "decode_call_us": round(dec_call_us, 2) if dec_call_us else None,
+        "prefill_tflops": round(pre_tflops, 1) if pre_tflops else None,
+        "prefill_ms": round(pre_t * 1e3, 3), "decode_ms": round(dec_t * 1e3, 3),
+        "roofline": dominant, "roofline_decode": roof_dec, "roofline_prefill": roof_pre,
+        "cpu_baseline": cpu,
+    }
+    duo.duo_cache_destroy(handle)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

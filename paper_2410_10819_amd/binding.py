@@ -90,6 +90,8 @@ def _ptr(t, name, dtype=None):
     """Device address of a contiguous torch CUDA tensor (None -> NULL)."""
     if t is None:
         return None
+    if isinstance(t, int):          # a raw device address the caller already validated
+        return ctypes.c_void_p(t)
     import torch
     if not isinstance(t, torch.Tensor) or not t.is_cuda:
         raise TypeError("%s must be a torch CUDA tensor" % name)
