@@ -146,10 +146,9 @@ def main():
 
     def decode_phase(timed):
         for t, (pq, pk, pv) in enumerate(dec_ptrs):
-            check(lib.duo_kv_append(handle, 0, pk, pv, 1, None, stream))
             if timed:
                 dec_events[t][0].record()
-            check(lib.duo_attn_decode(handle, 0, pq, None, None, None, p_out_dec, None, stream))
+            check(lib.duo_decode_step(handle, 0, pq, pk, pv, None, p_out_dec, None, stream))
             if timed:
                 dec_events[t][1].record()
 

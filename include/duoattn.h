@@ -126,6 +126,14 @@ int duo_attn_decode(duo_cache_t* cache, int layer, const void* q, const void* k,
                     const void* v, const duo_call_params_t* params, void* out,
                     float* lse, void* stream);
 
+/* duo_kv_append(n_new = 1) followed by duo_attn_decode(k = v = NULL), as ONE
+ * launch: the new token's rows are written into both caches (the length grows
+ * by one) while its query attends to the cache plus the new token.  k and v are
+ * required.  Same result as the two separate calls. */
+int duo_decode_step(duo_cache_t* cache, int layer, const void* q, const void* k,
+                    const void* v, const duo_call_params_t* params, void* out,
+                    float* lse, void* stream);
+
 /* Test hook: the tokens one (layer, sequence, KV head) cache currently holds, in
  * ascending position order.  k_out/v_out: device buffers of capacity
  * `capacity` rows, each row head_dim bf16 (DUO_KV_BF16) or head_dim bytes

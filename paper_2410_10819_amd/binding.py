@@ -13,7 +13,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libduoattn.so")
+LIB_PATH = os.environ.get("DUOATTN_LIB") or os.path.join(_HERE, "libduoattn.so")
 SYNTH_LIB_PATH = os.path.join(_HERE, "libduosynth.so")
 
 DUO_OK, DUO_EINVAL, DUO_ENOMEM, DUO_ERANGE, DUO_ESTATE, DUO_EHIP = 0, -1, -2, -3, -4, -5
@@ -64,6 +64,7 @@ def load() -> ctypes.CDLL:
     lib.duo_kv_append.argtypes = [vp, i32, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp]
     lib.duo_attn_prefill.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
     lib.duo_attn_decode.argtypes = [vp, i32, vp, vp, vp, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
+    lib.duo_decode_step.argtypes = lib.duo_attn_decode.argtypes
     lib.duo_cache_export.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, ctypes.POINTER(i64), vp]
     _lib = lib
     return lib
@@ -184,6 +185,14 @@ def duo_attn_decode(cache, layer, q, out, k=None, v=None, lse=None, params=None,
     import torch
     pp, keep = _params(params)
     _check(load().duo_attn_decode(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
+                                  _ptr(v, "v", torch.bfloat16), pp, _ptr(out, "out", torch.bfloat16),
+                                  _ptr(lse, "lse", torch.float32), _stream(stream)))
+
+
+def duo_decode_step(cache, layer, q, k, v, out, lse=None, params=None, stream=None):
+    import torch
+    pp, keep = _params(params)
+    _check(load().duo_decode_step(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
                                   _ptr(v, "v", torch.bfloat16), pp, _ptr(out, "out", torch.bfloat16),
                                   _ptr(lse, "lse", torch.float32), _stream(stream)))
 

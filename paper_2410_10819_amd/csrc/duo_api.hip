@@ -39,6 +39,7 @@ struct duo_cache {
   std::vector<void*> allocations;  // every device pointer owned by the handle
   float* part_o = nullptr;
   float* part_ml = nullptr;
+  int32_t* tickets = nullptr;
   int max_splits = 0;
   int user_splits = 0;
   int64_t cache_bytes = 0;
@@ -46,7 +47,7 @@ struct duo_cache {
 
 namespace {
 
-constexpr int kMaxSplits = 256;
+constexpr int kMaxSplits = duo::kMaxDecodeSplits;
 
 hipError_t dev_alloc(duo_cache* c, void** p, size_t bytes) {
   if (bytes == 0) bytes = 256;
@@ -88,7 +89,7 @@ int check_params(const duo_cache* c, int layer, const duo_call_params_t* p) {
 int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
   if (c->user_splits > 0) return c->user_splits < c->max_splits ? c->user_splits : c->max_splits;
   const int64_t kMinKeysPerSplit = 256;
-  const int64_t target_items = 1024;
+  const int64_t target_items = 256;
   int64_t heads = (int64_t)L.view.n_ret * c->cfg.batch;
   if (heads == 0) return 1;
   int64_t s = (target_items + heads - 1) / heads;
@@ -207,7 +208,11 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   c->max_splits = kMaxSplits;
   e = dev_alloc(c, (void**)&c->part_o, (size_t)cfg->batch * hq * c->max_splits * cfg->head_dim * sizeof(float));
   if (e == hipSuccess) e = dev_alloc(c, (void**)&c->part_ml, (size_t)cfg->batch * hq * c->max_splits * 2 * sizeof(float));
+  if (e == hipSuccess) e = dev_alloc(c, (void**)&c->tickets, (size_t)cfg->batch * hkv * sizeof(int32_t));
   if (e != hipSuccess) { release(c); return fail(DUO_ENOMEM, "hipMalloc(split-K scratch): %s", hipGetErrorString(e)); }
+  e = hipMemset(c->tickets, 0, (size_t)cfg->batch * hkv * sizeof(int32_t));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) { release(c); return fail_hip(e, "clearing the split-K tickets"); }
   *out = c;
   return DUO_OK;
 }
@@ -280,26 +285,37 @@ int duo_attn_prefill(duo_cache_t* c, int layer, const void* q, const void* k, co
   return DUO_OK;
 }
 
-int duo_attn_decode(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
-                    const duo_call_params_t* params, void* out, float* lse, void* stream) {
+static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                         const duo_call_params_t* params, void* out, float* lse, void* stream, bool commit) {
   int rc = check_handle_layer(c, layer);
   if (rc != DUO_OK) return rc;
   if (!q || !out) return fail(DUO_EINVAL, "q and out must not be NULL");
   if ((k == nullptr) != (v == nullptr)) return fail(DUO_EINVAL, "k and v must both be given or both be NULL");
+  if (commit && !k) return fail(DUO_EINVAL, "k and v must not be NULL");
   if ((rc = check_params(c, layer, params)) != DUO_OK) return rc;
   Layer& L = c->layers[layer];
   if (!k && L.len == 0) return fail(DUO_ESTATE, "decode on an empty cache needs the new token's k and v");
   if (k && L.len + 1 > c->cfg.max_seq)
     return fail(DUO_ERANGE, "decode at length %lld exceeds max_seq %lld", (long long)L.len, (long long)c->cfg.max_seq);
-  if (k && c->cfg.kv_dtype != DUO_KV_BF16)
-    return fail(DUO_EINVAL, "decode with an un-appended token supports bf16 caches only");
   duo::DecodeArgs a;
   a.lv = L.view; a.q = q; a.k_new = k; a.v_new = v; a.out = out; a.lse = lse;
-  a.part_o = c->part_o; a.part_ml = c->part_ml; a.cache_len = L.len;
+  a.part_o = c->part_o; a.part_ml = c->part_ml; a.tickets = c->tickets; a.cache_len = L.len;
   a.splits = choose_splits(c, L, L.len);
+  a.commit = commit ? 1 : 0;
   hipError_t e = duo::launch_decode(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "decode launch");
+  if (commit) L.len += 1;
   return DUO_OK;
+}
+
+int duo_attn_decode(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                    const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  return decode_common(c, layer, q, k, v, params, out, lse, stream, false);
+}
+
+int duo_decode_step(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                    const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  return decode_common(c, layer, q, k, v, params, out, lse, stream, true);
 }
 
 int duo_cache_export(duo_cache_t* c, int layer, int batch_idx, int kv_head, void* k_out, void* v_out,

@@ -13,6 +13,9 @@ namespace duo {
 // head's slot inside its class's cache.
 constexpr uint32_t kRetrievalBit = 0x80000000u;
 
+// Upper bound on key splits per retrieval head in decode (sizes the scratch).
+constexpr int kMaxDecodeSplits = 256;
+
 // Device view of one layer's two caches.  Layouts (row = one token of one head):
 //   retrieval: [batch][n_ret][max_seq][row_bytes]            (+ scales [batch][n_ret][max_seq])
 //   streaming: [batch][n_str][sink + recent][row_bytes]      (+ scales [batch][n_str][sink+recent])
@@ -49,8 +52,10 @@ struct DecodeArgs {
   float* lse;          // [batch][n_q_heads] or null
   float* part_o;       // [batch][n_q_heads][splits][head_dim]
   float* part_ml;      // [batch][n_q_heads][splits][2]
+  int32_t* tickets;    // [batch][n_kv_heads], zero between launches
   int64_t cache_len;   // tokens held by the cache
   int32_t splits;      // key splits per retrieval head
+  int32_t commit;      // write k_new / v_new into the caches (position cache_len)
 };
 
 struct PrefillArgs {

@@ -92,13 +92,16 @@ def run_scenario(duo, cfg, q_bits, k_bits, v_bits, chunks, n_decode, fused_decod
         qd, kd, vd = (to_dev(x[:, pos:pos + 1]) for x in (q_bits, k_bits, v_bits))
         od = torch.empty((b, 1, hq, d), dtype=torch.bfloat16, device="cuda")
         ld = torch.empty((b, hq), dtype=torch.float32, device="cuda") if want_lse else None
-        if fused_decode:
+        if fused_decode == "step":
+            duo.duo_decode_step(handle, 0, qd, kd, vd, od, lse=ld, params=params)
+        elif fused_decode:
             duo.duo_attn_decode(handle, 0, qd, od, k=kd, v=vd, lse=ld, params=params)
             duo.duo_kv_append(handle, 0, kd, vd, 1, params=params)
         else:
             duo.duo_kv_append(handle, 0, kd, vd, 1, params=params)
             duo.duo_attn_decode(handle, 0, qd, od, lse=ld, params=params)
         torch.cuda.synchronize()
+        assert duo.duo_cache_len(handle, 0) == pos + 1
         out[:, pos] = from_dev_bits(od)[:, 0]
         if want_lse:
             lse[:, :, pos] = ld.cpu().numpy()

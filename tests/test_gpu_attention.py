@@ -71,6 +71,61 @@ def test_mixed_heads_ragged_shapes(hq, hkv, d, sink, recent, chunks, n_decode, b
         duo.duo_cache_destroy(handle)
 
 
+@pytest.mark.parametrize("kv_dtype", [0, 1])
+@pytest.mark.parametrize("mode", [False, True, "step"])
+def test_three_decode_forms_agree_with_the_oracle(mode, kv_dtype):
+    # separate append + decode, un-committed k/v, and the one-launch step; the ring wraps
+    # several times and the retrieval cache crosses split boundaries
+    hq, hkv, d, sink, recent = 8, 4, 128, 4, 24
+    n_fill, n_decode = 600, 70
+    total = n_fill + n_decode
+    mask = np.array([1, 0, 0, 1], dtype=np.uint8)
+    cfg = dict(batch=2, hq=hq, hkv=hkv, d=d, sink=sink, recent=recent, mask=mask, max_seq=total, kv_dtype=kv_dtype)
+    q, k, v = make_qkv(77, 2, total, hq, hkv, d)
+    import torch
+    handle = duo.duo_cache_create(1, 2, hq, hkv, d, sink, recent, total, mask[None], kv_dtype)
+    try:
+        duo.duo_kv_append(handle, 0, to_dev(k[:, :n_fill]), to_dev(v[:, :n_fill]), n_fill)
+        got = np.zeros((2, n_decode, hq, d))
+        for t in range(n_decode):
+            p = n_fill + t
+            qd, kd, vd = (to_dev(x[:, p:p + 1]) for x in (q, k, v))
+            od = torch.empty((2, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+            if mode == "step":
+                duo.duo_decode_step(handle, 0, qd, kd, vd, od)
+            elif mode:
+                duo.duo_attn_decode(handle, 0, qd, od, k=kd, v=vd)
+                duo.duo_kv_append(handle, 0, kd, vd, 1)
+            else:
+                duo.duo_kv_append(handle, 0, kd, vd, 1)
+                duo.duo_attn_decode(handle, 0, qd, od)
+            got[:, t] = from_dev_f64(od)[:, 0]
+            assert duo.duo_cache_len(handle, 0) == p + 1
+        for b in range(2):
+            want_o, _ = oracle_rows(cfg, q, k, v, np.arange(n_fill, total), b)
+            assert_close(got[b], want_o, "mode %s batch %d" % (mode, b))
+        # the caches end up identical to what plain appends produce (bit-exact, via export)
+        pos_out = torch.empty(total, dtype=torch.int64, device="cuda")
+        for h in range(hkv):
+            dt = torch.uint8 if kv_dtype else torch.bfloat16
+            ko = torch.zeros((total, d), dtype=dt, device="cuda")
+            vo = torch.zeros((total, d), dtype=dt, device="cuda")
+            ks = torch.zeros(total, dtype=torch.float32, device="cuda") if kv_dtype else None
+            vs = torch.zeros(total, dtype=torch.float32, device="cuda") if kv_dtype else None
+            n = duo.duo_cache_export(handle, 0, 1, h, ko, vo, pos_out, total, kscale_out=ks, vscale_out=vs)
+            keep = oracle.retained_positions(total, sink, recent, bool(mask[h]))
+            assert pos_out[:n].cpu().tolist() == keep
+            want_k = k[1, keep, h]
+            if kv_dtype:
+                codes, scales = oracle.quantize_rows(synth.bf16_bits_to_f32(want_k))
+                assert np.array_equal(ko[:n].cpu().numpy(), codes)
+                assert np.array_equal(ks[:n].cpu().numpy().view(np.uint32), scales.view(np.uint32))
+            else:
+                assert np.array_equal(ko[:n].cpu().view(torch.int16).numpy().view(np.uint16), want_k)
+    finally:
+        duo.duo_cache_destroy(handle)
+
+
 @pytest.mark.parametrize("mask_kind", ["all_retrieval", "all_streaming"])
 def test_single_class_layers(mask_kind):
     hq, hkv, d, total = 4, 4, 64, 400
