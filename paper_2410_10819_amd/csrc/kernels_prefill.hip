@@ -4,13 +4,23 @@
 // (sink tokens + a window of `recent` positions ending at the query), so K/V
 // tiles outside the mask are never loaded.
 //
-// Flash-style kernel for CDNA4: one workgroup = 128 query rows of one query head
-// (4 wavefronts x 32 rows); K/V tiles of 64 keys staged in LDS; bf16 MFMA
-// 32x32x16 for both contractions with fp32 accumulation; online softmax in
+// Flash-style kernel for CDNA4.  A workgroup of four wavefronts owns a block of
+// query rows of one query head; every wavefront owns 64 rows (two 32-row
+// sub-blocks, so each K/V fragment read from LDS feeds two MFMAs and the softmax
+// arithmetic of one sub-block can overlap the matrix work of the other).  The
+// wavefronts form NG "key groups": with NG = 1 all four share each 64-key K/V
+// tile (256 rows per workgroup); with NG = 2 the two groups take alternate tiles
+// of the same 128 rows and their partial results are merged through LDS at the
+// end, which doubles the number of workgroups when a chunk has few row blocks.
+// K/V tiles are loaded straight from global memory into LDS (the lane-ordered
+// LDS-direct load; rows are stored with their 16-byte pieces XOR-swizzled so the
+// fragment reads are free of bank conflicts), double-buffered, the next tile's
+// loads being in flight while the current tile is computed.  Both contractions
+// use the bf16 MFMA 32x32x16 with fp32 accumulation; the softmax is online, in
 // registers.  The score tile is produced transposed (S^T = K Q^T) so that each
-// lane owns one query column: row statistics need a single cross-lane exchange,
-// and the accumulator registers of S^T are, after conversion to bf16, exactly
-// the B operand of O^T += V^T P^T.  V^T fragments come from LDS transpose reads.
+// lane owns one query column: row statistics need one cross-lane exchange, and
+// the accumulator registers of S^T are, after conversion to bf16, exactly the B
+// operand of O^T += V^T P^T.  V^T fragments come from LDS transpose reads.
 //
 // Keys are addressed through a "virtual key list" so that both head classes
 // share the code: for a retrieval head it is positions 0 .. pos0+n-1 (cache
@@ -27,14 +37,20 @@ constexpr float kLn2 = 0.6931471805599453f;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 64;   // keys per tile
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float swap_halves(float x, int peer_byte_addr) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(peer_byte_addr, __builtin_bit_cast(int, x)));
+}
+__device__ inline int clamp_i32(int64_t x) {
+  const int64_t lim = 1 << 30;
+  return (int)(x < -lim ? -lim : (x > lim ? lim : x));
+}
 
 // Where the keys of one (sequence, KV head) come from.
 struct KeySource {
@@ -48,35 +64,55 @@ struct KeySource {
   int64_t tail_pos;        // list entry n_head + x is position tail_pos + x
   int64_t total;           // list length
   int32_t sink, recent;
+  int32_t ring0;           // ring index (slot - sink) of position tail_pos
+  int32_t row_bytes;
   bool retrieval;
 
   __device__ inline int64_t position(int64_t u) const { return u < n_head ? u : tail_pos + (u - n_head); }
-  __device__ inline void rows(int64_t p, int row_bytes, const uint8_t*& kr, const uint8_t*& vr) const {
-    if (p >= pos0) {
-      kr = k_chunk + (p - pos0) * chunk_stride;
-      vr = v_chunk + (p - pos0) * chunk_stride;
-    } else {
-      int64_t slot = p;
-      if (!retrieval && p >= sink) slot = sink + (p - sink) % recent;
-      kr = k_cache + slot * row_bytes;
-      vr = v_cache + slot * row_bytes;
-    }
+  // Branch-free row addresses of position p (< pos0: cache slot; otherwise chunk row).
+  __device__ inline void rows(int64_t p, const uint8_t*& kr, const uint8_t*& vr) const {
+    const bool in_chunk = p >= pos0;
+    // cached ring positions are tail_pos .. pos0-1, fewer than `recent` of them
+    int64_t x = ring0 + (p - tail_pos);
+    if (x >= recent) x -= recent;
+    const int64_t slot = (retrieval || p < sink) ? p : sink + x;
+    const int64_t off = in_chunk ? (p - pos0) * chunk_stride : slot * row_bytes;
+    kr = (in_chunk ? k_chunk : k_cache) + off;
+    vr = (in_chunk ? v_chunk : v_cache) + off;
   }
 };
 
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
 template <int D>
+struct Geometry {
+  static constexpr int ROW = D * 2;                   // bytes per K or V row in LDS
+  static constexpr int TILE = BN * ROW;               // bytes of one K (or V) tile
+  static constexpr int BUF_BYTES = 2 * TILE;          // K tile then V tile
+  static constexpr int CPR = D / 8;                   // 16-byte pieces per row
+  // piece p of row r lives in slot p ^ swizzle(r)
+  __device__ static inline int k_swz(int row) { return row % CPR; }
+  __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
+};
+
+template <int D, int NG>
 __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
-  constexpr int KSTR = D * 2 + 16;  // LDS row strides chosen against bank conflicts
-  constexpr int VSTR = D * 2 + 64;
-  constexpr int NKK = D / 16;       // MFMA k-steps of the QK^T contraction
-  constexpr int NMB = D / 32;       // 32-row blocks of O^T
-  constexpr int CPR = D / 8;        // 16-byte pieces per row
-  __shared__ __attribute__((aligned(16))) uint8_t k_lds[BN * KSTR];
-  __shared__ __attribute__((aligned(16))) uint8_t v_lds[BN * VSTR];
+  using Geo = Geometry<D>;
+  constexpr int ROW = Geo::ROW, TILE = Geo::TILE, BUF_BYTES = Geo::BUF_BYTES;
+  constexpr int NKK = D / 16;          // MFMA k-steps of the QK^T contraction
+  constexpr int NMB = D / 32;          // 32-row blocks of O^T
+  constexpr int CPR = D / 8;           // 16-byte pieces per row
+  constexpr int WPG = 4 / NG;          // wavefronts per key group
+  constexpr int BM = 64 * WPG;         // query rows per workgroup
+  constexpr int RPWL = 1024 / ROW;     // rows covered by one wavefront-wide 1 KiB load
+  constexpr int NLOAD = TILE / 1024 / WPG;  // loads of K (and of V) per wavefront per tile
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
   const LayerView& lv = a.lv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = wave / WPG, wig = wave % WPG;
   const int col = lane & 31, half = lane >> 5;
+  const int peer = ((lane ^ 32) << 2);
   const int n_rb = (a.n + BM - 1) / BM;
   const int h = lv.q_order[blockIdx.x / n_rb];
   const int rb = n_rb - 1 - (int)(blockIdx.x % n_rb);   // longest rows first
@@ -88,7 +124,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
   KeySource ks;
   ks.retrieval = (info & kRetrievalBit) != 0;
   ks.pos0 = a.pos0;
-  ks.sink = lv.sink; ks.recent = lv.recent;
+  ks.sink = lv.sink; ks.recent = lv.recent; ks.row_bytes = lv.row_bytes; ks.ring0 = 0;
   ks.chunk_stride = (int64_t)lv.n_kv_heads * D * 2;
   ks.k_chunk = (const uint8_t*)a.k + ((int64_t)b * a.n * lv.n_kv_heads + kvh) * D * 2;
   ks.v_chunk = (const uint8_t*)a.v + ((int64_t)b * a.n * lv.n_kv_heads + kvh) * D * 2;
@@ -104,18 +140,27 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     const int64_t n_head = a.pos0 < lv.sink ? a.pos0 : lv.sink;
     const int64_t tail = a.pos0 - lv.recent > n_head ? a.pos0 - lv.recent : n_head;
     ks.n_head = n_head; ks.tail_pos = tail; ks.total = n_head + (a.pos0 + a.n - tail);
+    ks.ring0 = tail >= lv.sink ? (int32_t)((tail - lv.sink) % lv.recent) : 0;
   }
+  const int gap32 = (int)(ks.tail_pos - ks.n_head);
+  // list entries below sink_u are sink positions
+  const int64_t sink_u = gap32 == 0 ? (lv.sink < ks.total ? (int64_t)lv.sink : ks.total) : ks.n_head;
 
-  // Rows of this workgroup / wavefront / lane.
+  // Rows of this workgroup / wavefront / lane: sub-block sb covers chunk rows row_w + 32*sb + col.
   const int i_first = rb * BM;
   const int i_last = (i_first + BM < a.n ? i_first + BM : a.n) - 1;
   const int64_t qpos_first = a.pos0 + i_first, qpos_last = a.pos0 + i_last;
-  const int ci = i_first + wave * 32 + col;         // chunk index of this lane's query
-  const int ci_c = ci < a.n ? ci : a.n - 1;
-  const int64_t qpos = a.pos0 + ci_c;
-  const int64_t wave_qpos0 = a.pos0 + i_first + wave * 32;
+  const int row_w = i_first + wig * 64;
+  int ci[2];
+  int64_t qpos[2];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    ci[sb] = row_w + 32 * sb + col;
+    const int c = ci[sb] < a.n ? ci[sb] : a.n - 1;
+    qpos[sb] = a.pos0 + c;
+  }
 
-  // Tile ranges: [0, tA_end) covers the sink part, [tB_begin, t_end) the window.
+  // Tile list of the workgroup: [0, tA_end) covers the sink part, [tB_begin, t_end) the window.
   int64_t tA_end, tB_begin, t_end;
   if (ks.retrieval) {
     tA_end = 0; tB_begin = 0; t_end = qpos_last / BN + 1;
@@ -131,140 +176,261 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     t_end = u_hi / BN + 1;
     if (t_end < tA_end) t_end = tA_end;
   }
+  const int n_tiles = (int)(tA_end + (t_end - tB_begin));
+  const int n_iter = (n_tiles + NG - 1) / NG;
+  auto tile_of = [&](int s) -> int64_t { return s < tA_end ? (int64_t)s : tB_begin + (s - tA_end); };
 
-  // Q^T fragments (B operand): lane (col, half) holds q[ci][16*kk + 8*half .. +7].
-  bf16x8 qf[NKK];
-  {
-    const uint8_t* qrow = (const uint8_t*)a.q + (((int64_t)b * a.n + ci_c) * lv.n_q_heads + h) * D * 2;
+  // Q^T fragments (B operand): lane (col, half) holds q[row][16*kk + 8*half .. +7].
+  bf16x8 qf[2][NKK];
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8*)(qrow + (16 * kk + 8 * half) * 2);
+  for (int sb = 0; sb < 2; ++sb) {
+    const int c = ci[sb] < a.n ? ci[sb] : a.n - 1;
+    const uint8_t* qrow = (const uint8_t*)a.q + (((int64_t)b * a.n + c) * lv.n_q_heads + h) * D * 2;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) qf[sb][kk] = *(const bf16x8*)(qrow + (16 * kk + 8 * half) * 2);
   }
-  f32x16 o_acc[NMB];
+  f32x16 o_acc[2][NMB];
 #pragma unroll
-  for (int mb = 0; mb < NMB; ++mb)
+  for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o_acc[mb][r] = 0.f;
-  float m_i = -INFINITY, l_i = 0.f;
+    for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] = 0.f;
+  float m_i[2] = {-INFINITY, -INFINITY}, l_i[2] = {0.f, 0.f};
   const float sc = lv.scale * kLog2e;
 
-  for (int64_t t = 0; t < t_end; ++t) {
-    if (t == tA_end && t < tB_begin) t = tB_begin;
-    __syncthreads();
-    // Stage the tile: each thread moves 16-byte pieces of K and V rows.
+  // Issue the LDS-direct loads of tile t into a buffer: each wavefront-wide load
+  // fills 1 KiB (RPWL rows); lane (row, slot) fetches piece slot ^ swizzle(row).
+  auto fetch = [&](int64_t t, uint8_t* k_lds, uint8_t* v_lds) {
 #pragma unroll
-    for (int pass = 0; pass < BN * CPR / 256; ++pass) {
-      const int row = pass * (256 / CPR) + tid / CPR, piece = tid % CPR;
+    for (int x = 0; x < NLOAD; ++x) {
+      const int j = wig + WPG * x;
+      const int row = j * RPWL + lane / CPR, slot = lane % CPR;
       int64_t u = t * BN + row;
       if (u >= ks.total) u = ks.total - 1;
       const uint8_t *kr, *vr;
-      ks.rows(ks.position(u), lv.row_bytes, kr, vr);
-      const uint4 kc = *(const uint4*)(kr + piece * 16);
-      const uint4 vc = *(const uint4*)(vr + piece * 16);
-      *(uint4*)(k_lds + row * KSTR + piece * 16) = kc;
-      *(uint4*)(v_lds + row * VSTR + piece * 16) = vc;
+      ks.rows(ks.position(u), kr, vr);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kr + ((slot ^ Geo::k_swz(row)) * 16)), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vr + ((slot ^ Geo::v_swz(row)) * 16)), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
     }
-    __syncthreads();
+  };
 
-    // S^T = K Q^T : two 32-key blocks x 32 queries.
-    f32x16 s_acc[2];
+  if (grp < n_tiles) fetch(tile_of(grp), smem + (grp * 2) * BUF_BYTES, smem + (grp * 2) * BUF_BYTES + TILE);
+  for (int it = 0; it < n_iter; ++it) {
+    const int s = it * NG + grp;
+    const bool live = s < n_tiles;
+    uint8_t* k_lds = smem + (grp * 2 + (it & 1)) * BUF_BYTES;
+    uint8_t* v_lds = k_lds + TILE;
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's loads of the tile have landed in LDS
+    __syncthreads();
+    if (s + NG < n_tiles) {
+      uint8_t* nk = smem + (grp * 2 + ((it + 1) & 1)) * BUF_BYTES;
+      fetch(tile_of(s + NG), nk, nk + TILE);
+    }
+    if (!live) continue;
+    const int64_t t = tile_of(s);
+    const int64_t ub = t * BN;
+
+    // S^T = K Q^T : two 32-key blocks x (2 x 32) queries; each K fragment feeds both sub-blocks.
+    f32x16 s_acc[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.f;
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[sb][kb][r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
-        const bf16x8 kf = *(const bf16x8*)(k_lds + (32 * kb + col) * KSTR + (16 * kk + 8 * half) * 2);
-        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s_acc[kb], 0, 0, 0);
+        const bf16x8 kf = *(const bf16x8*)(k_lds + (32 * kb + col) * ROW + (((2 * kk + half) ^ Geo::k_swz(col)) * 16));
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+          s_acc[sb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[sb][kk], s_acc[sb][kb], 0, 0, 0);
       }
     }
-    // Mask (only tiles that touch the mask boundary or the end of the list).
-    const bool need_mask = !ks.retrieval || (t * BN + BN - 1 > wave_qpos0) || (t * BN + BN > ks.total);
-    if (need_mask) {
+
+    bf16x8 pf[2][4];
+#pragma unroll
+    for (int sbi = 0; sbi < 2; ++sbi) {
+#ifdef DUO_EXP_REV
+      const int sb = 1 - sbi;
+#else
+      const int sb = sbi;
+#endif
+      // Mask (only tiles that touch the mask boundary or the end of the list).
+      const int64_t sb_qpos0 = a.pos0 + row_w + 32 * sb;
+      const bool need_mask = !ks.retrieval || (ub + BN - 1 > sb_qpos0) || (ub + BN > ks.total);
+      // Scores of this sub-block with the mask applied, in registers of their own
+      // (the matrix-core accumulators are only read, never overwritten, here).
+      float sv[2][16];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sv[kb][r] = s_acc[sb][kb][r];
+      if (need_mask) {
+        const int lim = clamp_i32(ks.total - ub);
+        const int qa = clamp_i32(qpos[sb] - ub);             // query position relative to the tile
+        if (ks.retrieval) {
+          const int bound = qa < lim - 1 ? qa : lim - 1;     // visible iff u_rel <= bound
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int u_rel = 32 * kb + 8 * (r / 4) + 4 * half + (r % 4);
+              if (u_rel > bound) sv[kb][r] = -INFINITY;
+            }
+        } else {
+          const int nh_rel = clamp_i32(ks.n_head - ub);
+          const int sink_rel = clamp_i32(sink_u - ub);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int u_rel = 32 * kb + 8 * (r / 4) + 4 * half + (r % 4);
+              const int diff = qa - u_rel - (u_rel >= nh_rel ? gap32 : 0);   // query pos - key pos
+              const bool vis = u_rel < lim && diff >= 0 && (u_rel < sink_rel || diff < lv.recent);
+              if (!vis) sv[kb][r] = -INFINITY;
+            }
+        }
+      }
+      // Online softmax for this lane's query column.
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sv[kb][r]);
+      mx = fmaxf(mx, swap_halves(mx, peer));
+      const float m_new = fmaxf(m_i[sb], mx * sc);
+      const float mu = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = fast_exp2(m_i[sb] - mu);
+      m_i[sb] = m_new;
+      float psum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int64_t u = t * BN + 32 * kb + 8 * (r / 4) + 4 * half + (r % 4);
-          const int64_t p = ks.position(u);
-          const bool vis = u < ks.total && p <= qpos && (ks.retrieval || p < lv.sink || qpos - p < lv.recent);
-          if (!vis) s_acc[kb][r] = -INFINITY;
+          const float p = fast_exp2(fmaf(sv[kb][r], sc, -mu));
+          psum += p;
+          pf[sb][kb * 2 + r / 8][r % 8] = (__bf16)p;
         }
-    }
-    // Online softmax for this lane's query column.
-    float mx = -INFINITY;
+      l_i[sb] = l_i[sb] * alpha + psum;
+      if (__ballot(alpha != 1.0f) != 0) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+        for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_i, mx * sc);
-    const float mu = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = exp2f(m_i - mu);
-    m_i = m_new;
-    float psum = 0.f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(fmaf(s_acc[kb][r], sc, -mu));
-        psum += p;
-        pf[kb * 2 + r / 8][r % 8] = (__bf16)p;
+          for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] *= alpha;
       }
-    l_i = l_i * alpha + psum;
-    if (__ballot(alpha != 1.0f) != 0) {
-#pragma unroll
-      for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
     }
     // O^T += V^T P^T.  Slab sl covers keys 16*sl + {4*half + t, 8 + 4*half + t}.
     {
       const int blk = lane >> 4, l16 = lane & 15;
       const int e = l16 >> 2, i4 = l16 & 3;
-      const int dcol = 16 * (blk & 1) + 4 * i4;   // within the 32-row block of O^T
+      // this lane's 8 bytes sit in piece 4*mb + pc0 of row key0 (+8), at byte (i4 & 1) * 8 of the piece
+      const int pc0 = 2 * (blk & 1) + (i4 >> 1), sub8 = (i4 & 1) * 8;
 #pragma unroll
       for (int sl = 0; sl < 4; ++sl) {
         const int key0 = 16 * sl + 4 * half + e;
+        const int swz = Geo::v_swz(key0);   // rows key0 and key0 + 8 share the swizzle
 #pragma unroll
         for (int mb = 0; mb < NMB; ++mb) {
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              LDS_PTR(s16x4, v_lds + key0 * VSTR + (32 * mb + dcol) * 2));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              LDS_PTR(s16x4, v_lds + (key0 + 8) * VSTR + (32 * mb + dcol) * 2));
-          const s16x8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[sl], o_acc[mb], 0, 0, 0);
+          const int off = (((4 * mb + pc0) ^ swz) * 16) + sub8;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, v_lds + key0 * ROW + off));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, v_lds + (key0 + 8) * ROW + off));
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+          for (int sb = 0; sb < 2; ++sb)
+            o_acc[sb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sb][sl], o_acc[sb][mb], 0, 0, 0);
         }
       }
     }
   }
 
+  // Row sums over both lane halves.
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) l_i[sb] += swap_halves(l_i[sb], peer);
+
+  if constexpr (NG == 2) {
+    // Key group 1 hands its partial (O, m, l) to key group 0 through LDS.
+    constexpr int REGS = NMB * 16 + 2;
+    float* xch = (float*)smem;   // the tile buffers are free after the barrier
+    __syncthreads();
+    if (grp == 1) {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+        float* base = xch + ((wig * 2 + sb) * REGS) * 64 + lane;
+#pragma unroll
+        for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) base[(mb * 16 + r) * 64] = o_acc[sb][mb][r];
+        base[(NMB * 16) * 64] = m_i[sb];
+        base[(NMB * 16 + 1) * 64] = l_i[sb];
+      }
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const float* base = xch + ((wig * 2 + sb) * REGS) * 64 + lane;
+      const float m1 = base[(NMB * 16) * 64], l1 = base[(NMB * 16 + 1) * 64];
+      const float m_new = fmaxf(m_i[sb], m1);
+      const float mu = m_new == -INFINITY ? 0.f : m_new;
+      const float a0 = fast_exp2(m_i[sb] - mu), a1 = fast_exp2(m1 - mu);
+      l_i[sb] = l_i[sb] * a0 + l1 * a1;
+      m_i[sb] = m_new;
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] = o_acc[sb][mb][r] * a0 + base[(mb * 16 + r) * 64] * a1;
+    }
+  }
+
   // Normalise and store.  Lane (col, half) holds O^T rows 32*mb + 8*bq + 4*half + t.
-  const float l_tot = l_i + __shfl_xor(l_i, 32);
-  const float inv = 1.0f / l_tot;
-  if (ci < a.n) {
-    uint8_t* orow = (uint8_t*)a.out + (((int64_t)b * a.n + ci) * lv.n_q_heads + h) * D * 2;
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    if (ci[sb] >= a.n) continue;
+    const float inv = 1.0f / l_i[sb];
+    uint8_t* orow = (uint8_t*)a.out + (((int64_t)b * a.n + ci[sb]) * lv.n_q_heads + h) * D * 2;
 #pragma unroll
     for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
         bf16x4 w;
 #pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) w[t4] = (__bf16)(o_acc[mb][4 * bq + t4] * inv);
+        for (int t4 = 0; t4 < 4; ++t4) w[t4] = (__bf16)(o_acc[sb][mb][4 * bq + t4] * inv);
         *(bf16x4*)(orow + (32 * mb + 8 * bq + 4 * half) * 2) = w;
       }
-    if (a.lse && half == 0) a.lse[((int64_t)b * lv.n_q_heads + h) * a.n + ci] = (m_i + log2f(l_tot)) * kLn2;
+    if (a.lse && half == 0)
+      a.lse[((int64_t)b * lv.n_q_heads + h) * a.n + ci[sb]] = (m_i[sb] + log2f(l_i[sb])) * kLn2;
   }
+}
+
+template <int D, int NG>
+hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
+  constexpr int BM = 64 * (4 / NG);
+  constexpr int lds = NG * 2 * Geometry<D>::BUF_BYTES;
+  static bool configured = false;   // one attribute call per kernel instantiation and process
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<D, NG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int n_rb = (a.n + BM - 1) / BM;
+  dim3 grid((unsigned)(n_rb * a.lv.n_q_heads), a.lv.batch);
+  prefill_kernel<D, NG><<<grid, 256, lds, stream>>>(a);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
-  const int n_rb = (a.n + BM - 1) / BM;
-  dim3 grid((unsigned)(n_rb * a.lv.n_q_heads), a.lv.batch);
-  if (a.lv.head_dim == 128) prefill_kernel<128><<<grid, 256, 0, stream>>>(a);
-  else prefill_kernel<64><<<grid, 256, 0, stream>>>(a);
-  return hipGetLastError();
+  // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
+  const int64_t heavy_blocks = (int64_t)a.lv.batch * a.lv.n_ret * a.lv.group * ((a.n + 255) / 256);
+#ifdef DUO_EXP_NG1
+  const bool split_keys = false;
+#else
+  const bool split_keys = heavy_blocks < 384;
+#endif
+  if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2>(a, stream) : launch_one<128, 1>(a, stream);
+  return split_keys ? launch_one<64, 2>(a, stream) : launch_one<64, 1>(a, stream);
 }
 
 }  // namespace duo
