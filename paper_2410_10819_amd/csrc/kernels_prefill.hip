@@ -95,15 +95,17 @@ struct Geometry {
   __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
 };
 
-template <int D, int NG>
-__global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
+template <int D, int NG, int NSB>
+__global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillArgs a) {
   using Geo = Geometry<D>;
   constexpr int ROW = Geo::ROW, TILE = Geo::TILE, BUF_BYTES = Geo::BUF_BYTES;
   constexpr int NKK = D / 16;          // MFMA k-steps of the QK^T contraction
   constexpr int NMB = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;           // 16-byte pieces per row
-  constexpr int WPG = 4 / NG;          // wavefronts per key group
-  constexpr int BM = 64 * WPG;         // query rows per workgroup
+  constexpr int NW = NSB == 2 ? 4 : 8; // wavefronts per workgroup: 64 rows each, or 32 rows each at two per SIMD
+  constexpr int WPG = NW / NG;         // wavefronts per key group
+  constexpr int RW = 32 * NSB;         // query rows per wavefront
+  constexpr int BM = RW * WPG;         // query rows per workgroup
   constexpr int RPWL = 1024 / ROW;     // rows covered by one wavefront-wide 1 KiB load
   constexpr int NLOAD = TILE / 1024 / WPG;  // loads of K (and of V) per wavefront per tile
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -150,11 +152,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
   const int i_first = rb * BM;
   const int i_last = (i_first + BM < a.n ? i_first + BM : a.n) - 1;
   const int64_t qpos_first = a.pos0 + i_first, qpos_last = a.pos0 + i_last;
-  const int row_w = i_first + wig * 64;
-  int ci[2];
-  int64_t qpos[2];
+  const int row_w = i_first + wig * RW;
+  int ci[NSB];
+  int64_t qpos[NSB];
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
+  for (int sb = 0; sb < NSB; ++sb) {
     ci[sb] = row_w + 32 * sb + col;
     const int c = ci[sb] < a.n ? ci[sb] : a.n - 1;
     qpos[sb] = a.pos0 + c;
@@ -181,22 +183,24 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
   auto tile_of = [&](int s) -> int64_t { return s < tA_end ? (int64_t)s : tB_begin + (s - tA_end); };
 
   // Q^T fragments (B operand): lane (col, half) holds q[row][16*kk + 8*half .. +7].
-  bf16x8 qf[2][NKK];
+  bf16x8 qf[NSB][NKK];
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
+  for (int sb = 0; sb < NSB; ++sb) {
     const int c = ci[sb] < a.n ? ci[sb] : a.n - 1;
     const uint8_t* qrow = (const uint8_t*)a.q + (((int64_t)b * a.n + c) * lv.n_q_heads + h) * D * 2;
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) qf[sb][kk] = *(const bf16x8*)(qrow + (16 * kk + 8 * half) * 2);
   }
-  f32x16 o_acc[2][NMB];
+  f32x16 o_acc[NSB][NMB];
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb)
+  for (int sb = 0; sb < NSB; ++sb)
 #pragma unroll
     for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] = 0.f;
-  float m_i[2] = {-INFINITY, -INFINITY}, l_i[2] = {0.f, 0.f};
+  float m_i[NSB], l_i[NSB];
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb) { m_i[sb] = -INFINITY; l_i[sb] = 0.f; }
   const float sc = lv.scale * kLog2e;
 
   // Issue the LDS-direct loads of tile t into a buffer: each wavefront-wide load
@@ -232,30 +236,25 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     const int64_t ub = t * BN;
 
     // S^T = K Q^T : two 32-key blocks x (2 x 32) queries; each K fragment feeds both sub-blocks.
-    f32x16 s_acc[2][2];
+    f32x16 s_acc[NSB][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
+      for (int sb = 0; sb < NSB; ++sb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_acc[sb][kb][r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
         const bf16x8 kf = *(const bf16x8*)(k_lds + (32 * kb + col) * ROW + (((2 * kk + half) ^ Geo::k_swz(col)) * 16));
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
+        for (int sb = 0; sb < NSB; ++sb)
           s_acc[sb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[sb][kk], s_acc[sb][kb], 0, 0, 0);
       }
     }
 
-    bf16x8 pf[2][4];
+    bf16x8 pf[NSB][4];
 #pragma unroll
-    for (int sbi = 0; sbi < 2; ++sbi) {
-#ifdef DUO_EXP_REV
-      const int sb = 1 - sbi;
-#else
-      const int sb = sbi;
-#endif
+    for (int sb = 0; sb < NSB; ++sb) {
       // Mask (only tiles that touch the mask boundary or the end of the list).
       const int64_t sb_qpos0 = a.pos0 + row_w + 32 * sb;
       const bool need_mask = !ks.retrieval || (ub + BN - 1 > sb_qpos0) || (ub + BN > ks.total);
@@ -337,7 +336,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
           const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, v_lds + (key0 + 8) * ROW + off));
           const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-          for (int sb = 0; sb < 2; ++sb)
+          for (int sb = 0; sb < NSB; ++sb)
             o_acc[sb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sb][sl], o_acc[sb][mb], 0, 0, 0);
         }
       }
@@ -346,7 +345,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
 
   // Row sums over both lane halves.
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb) l_i[sb] += swap_halves(l_i[sb], peer);
+  for (int sb = 0; sb < NSB; ++sb) l_i[sb] += swap_halves(l_i[sb], peer);
 
   if constexpr (NG == 2) {
     // Key group 1 hands its partial (O, m, l) to key group 0 through LDS.
@@ -355,8 +354,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     __syncthreads();
     if (grp == 1) {
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb) {
-        float* base = xch + ((wig * 2 + sb) * REGS) * 64 + lane;
+      for (int sb = 0; sb < NSB; ++sb) {
+        float* base = xch + ((wig * NSB + sb) * REGS) * 64 + lane;
 #pragma unroll
         for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
@@ -368,8 +367,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     __syncthreads();
     if (grp == 1) return;
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      const float* base = xch + ((wig * 2 + sb) * REGS) * 64 + lane;
+    for (int sb = 0; sb < NSB; ++sb) {
+      const float* base = xch + ((wig * NSB + sb) * REGS) * 64 + lane;
       const float m1 = base[(NMB * 16) * 64], l1 = base[(NMB * 16 + 1) * 64];
       const float m_new = fmaxf(m_i[sb], m1);
       const float mu = m_new == -INFINITY ? 0.f : m_new;
@@ -385,7 +384,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
 
   // Normalise and store.  Lane (col, half) holds O^T rows 32*mb + 8*bq + 4*half + t.
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
+  for (int sb = 0; sb < NSB; ++sb) {
     if (ci[sb] >= a.n) continue;
     const float inv = 1.0f / l_i[sb];
     uint8_t* orow = (uint8_t*)a.out + (((int64_t)b * a.n + ci[sb]) * lv.n_q_heads + h) * D * 2;
@@ -403,34 +402,36 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-template <int D, int NG>
+template <int D, int NG, int NSB>
 hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
-  constexpr int BM = 64 * (4 / NG);
+  constexpr int NW = NSB == 2 ? 4 : 8;
+  constexpr int BM = 32 * NSB * (NW / NG);
   constexpr int lds = NG * 2 * Geometry<D>::BUF_BYTES;
   static bool configured = false;   // one attribute call per kernel instantiation and process
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<D, NG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<D, NG, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int n_rb = (a.n + BM - 1) / BM;
   dim3 grid((unsigned)(n_rb * a.lv.n_q_heads), a.lv.batch);
-  prefill_kernel<D, NG><<<grid, 256, lds, stream>>>(a);
+  prefill_kernel<D, NG, NSB><<<grid, NW * 64, lds, stream>>>(a);
   return hipGetLastError();
 }
+
+#ifndef DUO_EXP_NSB
+#define DUO_EXP_NSB 1
+#endif
 
 }  // namespace
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
   const int64_t heavy_blocks = (int64_t)a.lv.batch * a.lv.n_ret * a.lv.group * ((a.n + 255) / 256);
-#ifdef DUO_EXP_NG1
-  const bool split_keys = false;
-#else
   const bool split_keys = heavy_blocks < 384;
-#endif
-  if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2>(a, stream) : launch_one<128, 1>(a, stream);
-  return split_keys ? launch_one<64, 2>(a, stream) : launch_one<64, 1>(a, stream);
+  constexpr int NSB = DUO_EXP_NSB;
+  if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB>(a, stream) : launch_one<128, 1, NSB>(a, stream);
+  return split_keys ? launch_one<64, 2, NSB>(a, stream) : launch_one<64, 1, NSB>(a, stream);
 }
 
 }  // namespace duo
