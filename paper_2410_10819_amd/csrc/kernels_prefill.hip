@@ -36,6 +36,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -205,17 +206,55 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
 
   // Issue the LDS-direct loads of tile t into a buffer: each wavefront-wide load
   // fills 1 KiB (RPWL rows); lane (row, slot) fetches piece slot ^ swizzle(row).
+  // A tile whose 64 keys are consecutive rows of one region (the dense cache of a
+  // retrieval head, or the chunk) is addressed as a wavefront-uniform base plus
+  // per-lane offsets that never change; other tiles take the general path.
+  // (Successive loads of a wavefront are WPG * RPWL rows apart, a multiple of the
+  // swizzle period, so one set of lane offsets serves all of them.)
+  static_assert((WPG * RPWL) % CPR == 0 || (RPWL % CPR) == 0, "swizzle must not depend on the load index");
+  constexpr int XROWS = WPG * RPWL;    // rows between successive loads of one wavefront
+  int lin_k_cache, lin_v_cache, lin_k_chunk, lin_v_chunk;
+  {
+    const int row = wig * RPWL + lane / CPR, slot = lane % CPR;
+    lin_k_cache = row * ROW + ((slot ^ Geo::k_swz(row)) * 16);
+    lin_v_cache = row * ROW + ((slot ^ Geo::v_swz(row)) * 16);
+    lin_k_chunk = row * (int)ks.chunk_stride + ((slot ^ Geo::k_swz(row)) * 16);
+    lin_v_chunk = row * (int)ks.chunk_stride + ((slot ^ Geo::v_swz(row)) * 16);
+  }
   auto fetch = [&](int64_t t, uint8_t* k_lds, uint8_t* v_lds) {
+    const int64_t u0 = t * BN;
+    const bool whole = u0 + BN <= ks.total;
+    if (whole && ks.retrieval && u0 + BN <= ks.pos0) {          // dense cache rows u0 .. u0+63
+      const uint8_t* kb = ks.k_cache + u0 * ROW;
+      const uint8_t* vb = ks.v_cache + u0 * ROW;
 #pragma unroll
-    for (int x = 0; x < NLOAD; ++x) {
-      const int j = wig + WPG * x;
-      const int row = j * RPWL + lane / CPR, slot = lane % CPR;
-      int64_t u = t * BN + row;
-      if (u >= ks.total) u = ks.total - 1;
-      const uint8_t *kr, *vr;
-      ks.rows(ks.position(u), kr, vr);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kr + ((slot ^ Geo::k_swz(row)) * 16)), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vr + ((slot ^ Geo::v_swz(row)) * 16)), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
+      for (int x = 0; x < NLOAD; ++x) {
+        const int j = wig + WPG * x;
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb + x * XROWS * ROW + lin_k_cache), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb + x * XROWS * ROW + lin_v_cache), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
+      }
+    } else if (whole && ks.position(u0) >= ks.pos0) {           // chunk rows
+      const int64_t c0 = ks.position(u0) - ks.pos0;
+      const uint8_t* kb = ks.k_chunk + c0 * ks.chunk_stride;
+      const uint8_t* vb = ks.v_chunk + c0 * ks.chunk_stride;
+#pragma unroll
+      for (int x = 0; x < NLOAD; ++x) {
+        const int j = wig + WPG * x;
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb + x * XROWS * ks.chunk_stride + lin_k_chunk), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb + x * XROWS * ks.chunk_stride + lin_v_chunk), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
+      }
+    } else {                                                    // rare: not unrolled, to keep registers free
+#pragma nounroll
+      for (int x = 0; x < NLOAD; ++x) {
+        const int j = wig + WPG * x;
+        const int row = j * RPWL + lane / CPR, slot = lane % CPR;
+        int64_t u = u0 + row;
+        if (u >= ks.total) u = ks.total - 1;
+        const uint8_t *kr, *vr;
+        ks.rows(ks.position(u), kr, vr);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kr + ((slot ^ Geo::k_swz(row)) * 16)), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vr + ((slot ^ Geo::v_swz(row)) * 16)), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
+      }
     }
   };
 
@@ -252,14 +291,52 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
       }
     }
 
+    // Keep the three phases (scores, softmax, PV) apart in the instruction stream:
+    // hoisting the next phase's LDS reads over the current phase costs more
+    // registers than this kernel has at two wavefronts per SIMD.
+    __builtin_amdgcn_sched_barrier(0);
     bf16x8 pf[NSB][4];
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       // Mask (only tiles that touch the mask boundary or the end of the list).
       const int64_t sb_qpos0 = a.pos0 + row_w + 32 * sb;
       const bool need_mask = !ks.retrieval || (ub + BN - 1 > sb_qpos0) || (ub + BN > ks.total);
-      // Scores of this sub-block with the mask applied, in registers of their own
-      // (the matrix-core accumulators are only read, never overwritten, here).
+      // Online softmax for this lane's query column; `score(kb, r)` yields the masked score.
+      auto softmax_block = [&](auto&& score) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, score(kb, r));
+        mx = fmaxf(mx, swap_halves(mx, peer));
+        const float m_new = fmaxf(m_i[sb], mx * sc);
+        const float mu = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = fast_exp2(m_i[sb] - mu);
+        m_i[sb] = m_new;
+        float psum = 0.f;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            const float p0 = fast_exp2(fmaf(score(kb, r), sc, -mu));
+            const float p1 = fast_exp2(fmaf(score(kb, r + 1), sc, -mu));
+            const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+            // the row sum is taken over the rounded probabilities the PV product uses
+            psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);
+            pf[sb][kb * 2 + r / 8][r % 8] = pp[0];
+            pf[sb][kb * 2 + r / 8][r % 8 + 1] = pp[1];
+          }
+        l_i[sb] = l_i[sb] * alpha + psum;
+        if (__ballot(alpha != 1.0f) != 0) {
+#pragma unroll
+          for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] *= alpha;
+        }
+      };
+      // Scores with the mask applied, in registers of their own: the matrix-core
+      // accumulators are only read here, never overwritten.
       float sv[2][16];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -291,34 +368,9 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
             }
         }
       }
-      // Online softmax for this lane's query column.
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sv[kb][r]);
-      mx = fmaxf(mx, swap_halves(mx, peer));
-      const float m_new = fmaxf(m_i[sb], mx * sc);
-      const float mu = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = fast_exp2(m_i[sb] - mu);
-      m_i[sb] = m_new;
-      float psum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = fast_exp2(fmaf(sv[kb][r], sc, -mu));
-          psum += p;
-          pf[sb][kb * 2 + r / 8][r % 8] = (__bf16)p;
-        }
-      l_i[sb] = l_i[sb] * alpha + psum;
-      if (__ballot(alpha != 1.0f) != 0) {
-#pragma unroll
-        for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] *= alpha;
-      }
+      softmax_block([&](int kb, int r) { return sv[kb][r]; });
     }
+    __builtin_amdgcn_sched_barrier(0);
     // O^T += V^T P^T.  Slab sl covers keys 16*sl + {4*half + t, 8 + 4*half + t}.
     {
       const int blk = lane >> 4, l16 = lane & 15;
@@ -428,7 +480,11 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
   const int64_t heavy_blocks = (int64_t)a.lv.batch * a.lv.n_ret * a.lv.group * ((a.n + 255) / 256);
+#ifdef DUO_EXP_NG1
+  const bool split_keys = false;
+#else
   const bool split_keys = heavy_blocks < 384;
+#endif
   constexpr int NSB = DUO_EXP_NSB;
   if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB>(a, stream) : launch_one<128, 1, NSB>(a, stream);
   return split_keys ? launch_one<64, 2, NSB>(a, stream) : launch_one<64, 1, NSB>(a, stream);

@@ -8,7 +8,9 @@ from paper_2410_10819_amd import synth
 
 ATOL_MAX = 2e-2     # max-abs bound on bf16 attention outputs vs the float64 oracle
 ATOL_MEAN = 2e-3    # mean-abs bound
-ATOL_LSE = 1e-3
+# log-sum-exp: the kernels sum the bf16-rounded probabilities they feed to the PV product
+# (relative rounding error <= 2^-9 per term), so |lse - exact| <= 2^-9 = 1.95e-3 plus fp32 noise
+ATOL_LSE = 2.5e-3
 
 
 def to_dev(bits: np.ndarray):
