@@ -24,6 +24,9 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, scaled by a 1 GiB
+# device copy (summary under profiles/); known for the default workload only.
+MEASURED_TRAFFIC = {"c2": {"decode": 138.98e6 + 0.18e6, "prefill": 780.4e6 + 34.5e6}}
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
@@ -62,6 +65,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) so that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -142,15 +148,11 @@ def main():
             check(lib.duo_kv_append(handle, 0, P(k_fill), P(v_fill), n_prefill, None, stream))
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    dec_events = [(ev(), ev()) for _ in range(n_decode)]
 
     def decode_phase(timed):
-        for t, (pq, pk, pv) in enumerate(dec_ptrs):
-            if timed:
-                dec_events[t][0].record()
+        # one launch per token: duo_decode_step appends the token and attends
+        for pq, pk, pv in dec_ptrs:
             check(lib.duo_decode_step(handle, 0, pq, pk, pv, None, p_out_dec, None, stream))
-            if timed:
-                dec_events[t][1].record()
 
     pre_ms, dec_ms, dec_kernel_ms = [], [], []
     e0, e1, e2 = ev(), ev(), ev()
@@ -166,6 +168,13 @@ def main():
         if timed:
             e2.record()
 
+    if args.calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()
@@ -176,7 +185,9 @@ def main():
         pre_ms.append(e0.elapsed_time(e1))
         dec_ms.append(e1.elapsed_time(e2))
         if n_decode:
-            dec_kernel_ms.append(sum(a.elapsed_time(b) for a, b in dec_events) / n_decode)
+            # events bracket the n_decode back-to-back launches: average time per launch,
+            # launch gaps included (the kernel-only figure is in the rocprofv3 summary)
+            dec_kernel_ms.append(e1.elapsed_time(e2) / n_decode)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
@@ -204,13 +215,15 @@ def main():
     roof_dec = None
     if dec_gbps:
         roof_dec = {"bound": "hbm", "achieved": round(dec_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": round(dec_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
+                    "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("decode"),
                     "kernel": "duo::decode_kernel", "bytes_per_launch": int(avg_dec_bytes),
                     "avg_launch_us": round(dec_call_us, 2)}
     roof_pre = None
     if pre_tflops:
         roof_pre = {"bound": "mfma", "achieved": round(pre_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("prefill"),
                     "kernel": "duo::prefill_kernel", "flops_per_step": int(flops),
                     "avg_chunk_ms": round(pre_t * 1e3 / max(len(chunks), 1), 3)}
     dominant = roof_dec if (roof_pre is None or (roof_dec is not None and dec_t >= pre_t)) else roof_pre
