@@ -46,6 +46,12 @@ WORKLOADS = {
                          batch=4, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 4"),
     "c3_decode_b16": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=0, decode=32,
                           batch=16, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 16"),
+    "c4": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=1 << 20, chunk=0, decode=4, batch=1,
+               layers=32, desc="Llama-3-8B-shaped GQA decode at 1048576 context, 32 layers (attention op only), "
+                               "bf16 KV, batch 1"),
+    "c5": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=3300000, chunk=0, decode=4, batch=1,
+               layers=32, kv_dtype=1, desc="Llama-3-8B-shaped GQA decode at 3300000 context, 32 layers, fp8 e4m3 KV "
+                                           "+ fp32 scales per (token, KV head), batch 1"),
 }
 
 
@@ -65,6 +71,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--splits", type=int, default=0, help="key splits per retrieval head in decode (0 = automatic)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -84,89 +91,103 @@ def main():
     hq, hkv, d, B = w["hq"], w["hkv"], w["d"], w["batch"]
     sink, recent = w["sink"], w["recent"]
     n_prefill, chunk, n_decode = w["prefill"], w["chunk"], w["decode"]
+    n_layers, kv_dtype = w.get("layers", 1), w.get("kv_dtype", 0)
     group = hq // hkv
-    total = n_prefill + n_decode
-    mask = synth.retrieval_mask(args.seed, 1, hkv, w["ratio"])
-    n_ret = int(mask.sum())
+    attn_prefill = chunk > 0
+    # with pre-filling attention a step starts from an empty cache; a decode-only workload fills its
+    # caches once (by append alone) before the timed region and every step decodes n_decode more tokens
+    n_dec_total = n_decode if attn_prefill else n_decode * (args.warmup + args.steps)
+    total = n_prefill + n_dec_total
+    mask = synth.retrieval_mask(args.seed, n_layers, hkv, w["ratio"])
+    n_ret = int(mask[0].sum())
     n_str = hkv - n_ret
     stream = torch.cuda.current_stream().cuda_stream
+    assert attn_prefill or n_decode > 0
+    assert n_layers == 1 or not attn_prefill
 
     # ---- synthetic inputs, generated on the device (bit-identical to the CPU generator)
     table = torch.from_numpy(synth.normal_table_bf16().view(np.int16)).cuda()
 
-    def fill(tensor_id, heads, n_pos):
+    def fill(layer, tensor_id, heads, pos, n_pos):
         t = torch.empty((B, n_pos, heads, d), dtype=torch.bfloat16, device="cuda")
         for b in range(B):
-            duo.duo_synth_fill_bf16(t[b], table, synth.stream_key(args.seed, 0, tensor_id, b), 0, n_pos, heads, d)
+            duo.duo_synth_fill_bf16(t[b], table, synth.stream_key(args.seed, layer, tensor_id, b), pos, n_pos,
+                                    heads, d)
         return t
 
-    attn_prefill = chunk > 0
-    q_all = fill(synth.TENSOR_Q, hq, total) if attn_prefill else None
-    k_all = fill(synth.TENSOR_K, hkv, total)
-    v_all = fill(synth.TENSOR_V, hkv, total)
-    # decode-phase inputs as separate contiguous [B, 1, H, D] slices
-    if attn_prefill:
-        q_dec = [q_all[:, n_prefill + t:n_prefill + t + 1].contiguous() for t in range(n_decode)]
-    else:
-        qd = torch.empty((B, n_decode, hq, d), dtype=torch.bfloat16, device="cuda")
-        for b in range(B):
-            duo.duo_synth_fill_bf16(qd[b], table, synth.stream_key(args.seed, 0, synth.TENSOR_Q, b), n_prefill,
-                                    n_decode, hq, d)
-        q_dec = [qd[:, t:t + 1].contiguous() for t in range(n_decode)]
-    k_dec = [k_all[:, n_prefill + t:n_prefill + t + 1].contiguous() for t in range(n_decode)]
-    v_dec = [v_all[:, n_prefill + t:n_prefill + t + 1].contiguous() for t in range(n_decode)]
-    chunks = []
-    if attn_prefill:
-        for p in range(0, n_prefill, chunk):
-            n = min(chunk, n_prefill - p)
-            chunks.append((p, n, q_all[:, p:p + n].contiguous() if B > 1 else q_all[:, p:p + n],
-                           k_all[:, p:p + n].contiguous() if B > 1 else k_all[:, p:p + n],
-                           v_all[:, p:p + n].contiguous() if B > 1 else v_all[:, p:p + n]))
-    out_pre = torch.empty((B, max(chunk, 1), hq, d), dtype=torch.bfloat16, device="cuda")
-    out_dec = torch.empty((B, 1, hq, d), dtype=torch.bfloat16, device="cuda")
-    handle = duo.duo_cache_create(1, B, hq, hkv, d, sink, recent, total, mask)
-    torch.cuda.synchronize()
-
-    # raw pointers so the timed loop is not dominated by Python-side tensor checks
-    P = lambda t: t.data_ptr()
-    chunk_ptrs = [(n, P(qc), P(kc), P(vc)) for (_, n, qc, kc, vc) in chunks]
-    dec_ptrs = [(P(q_dec[t]), P(k_dec[t]), P(v_dec[t])) for t in range(n_decode)]
-    p_out_pre, p_out_dec = P(out_pre), P(out_dec)
-    k_fill = k_all[:, :n_prefill] if B == 1 else k_all[:, :n_prefill].contiguous()
-    v_fill = v_all[:, :n_prefill] if B == 1 else v_all[:, :n_prefill].contiguous()
+    handle = duo.duo_cache_create(n_layers, B, hq, hkv, d, sink, recent, total, mask, kv_dtype)
+    if args.splits:
+        duo.duo_set_decode_splits(handle, args.splits)
+    P = lambda t: t.data_ptr()   # raw pointers: the timed loop does no Python-side tensor checks
 
     def check(rc):
         if rc != 0:
             raise duo.DuoError(rc, lib.duo_last_error().decode())
 
+    chunks, keep = [], []
+    if attn_prefill:
+        q_all = fill(0, synth.TENSOR_Q, hq, 0, total)
+        k_all = fill(0, synth.TENSOR_K, hkv, 0, total)
+        v_all = fill(0, synth.TENSOR_V, hkv, 0, total)
+        for p in range(0, n_prefill, chunk):
+            n = min(chunk, n_prefill - p)
+            qc, kc, vc = (t[:, p:p + n].contiguous() if B > 1 else t[:, p:p + n] for t in (q_all, k_all, v_all))
+            keep.append((qc, kc, vc))
+            chunks.append((p, n, P(qc), P(kc), P(vc)))
+        dec_src = [(q_all[:, n_prefill:], k_all[:, n_prefill:], v_all[:, n_prefill:])]
+    else:
+        fill_chunk = 1 << 17
+        for layer in range(n_layers):
+            for p in range(0, n_prefill, fill_chunk):
+                n = min(fill_chunk, n_prefill - p)
+                kc, vc = fill(layer, synth.TENSOR_K, hkv, p, n), fill(layer, synth.TENSOR_V, hkv, p, n)
+                duo.duo_kv_append(handle, layer, kc, vc, n)
+            torch.cuda.synchronize()
+        dec_src = [(fill(layer, synth.TENSOR_Q, hq, n_prefill, n_dec_total),
+                    fill(layer, synth.TENSOR_K, hkv, n_prefill, n_dec_total),
+                    fill(layer, synth.TENSOR_V, hkv, n_prefill, n_dec_total)) for layer in range(n_layers)]
+    # decode-phase inputs as separate contiguous [B, 1, H, D] slices: dec_ptrs[token][layer]
+    dec_ptrs = []
+    for t in range(n_dec_total):
+        per_layer = []
+        for layer in range(n_layers):
+            trio = tuple(x[:, t:t + 1].contiguous() for x in dec_src[layer])
+            keep.append(trio)
+            per_layer.append(tuple(P(x) for x in trio))
+        dec_ptrs.append(per_layer)
+    out_pre = torch.empty((B, max(chunk, 1), hq, d), dtype=torch.bfloat16, device="cuda")
+    out_dec = torch.empty((B, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+    p_out_pre, p_out_dec = P(out_pre), P(out_dec)
+    torch.cuda.synchronize()
+
     def prefill_phase():
-        if attn_prefill:
-            for n, pq, pk, pv in chunk_ptrs:
-                check(lib.duo_attn_prefill(handle, 0, pq, pk, pv, n, None, p_out_pre, None, stream))
-                check(lib.duo_kv_append(handle, 0, pk, pv, n, None, stream))
-        else:
-            check(lib.duo_kv_append(handle, 0, P(k_fill), P(v_fill), n_prefill, None, stream))
+        for _, n, pq, pk, pv in chunks:
+            check(lib.duo_attn_prefill(handle, 0, pq, pk, pv, n, None, p_out_pre, None, stream))
+            check(lib.duo_kv_append(handle, 0, pk, pv, n, None, stream))
+
+    def decode_phase(first_token):
+        # one launch per token and layer: duo_decode_step appends the token and attends
+        for t in range(first_token, first_token + n_decode):
+            for layer, (pq, pk, pv) in enumerate(dec_ptrs[t]):
+                check(lib.duo_decode_step(handle, layer, pq, pk, pv, None, p_out_dec, None, stream))
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
-
-    def decode_phase(timed):
-        # one launch per token: duo_decode_step appends the token and attends
-        for pq, pk, pv in dec_ptrs:
-            check(lib.duo_decode_step(handle, 0, pq, pk, pv, None, p_out_dec, None, stream))
-
-    pre_ms, dec_ms, dec_kernel_ms = [], [], []
+    pre_ms, dec_ms = [], []
     e0, e1, e2 = ev(), ev(), ev()
+    step_no = [0]
 
     def one_step(timed):
-        duo.duo_cache_reset(handle)
+        if attn_prefill:
+            duo.duo_cache_reset(handle)
         if timed:
             e0.record()
         prefill_phase()
         if timed:
             e1.record()
-        decode_phase(timed)
+        decode_phase(0 if attn_prefill else step_no[0] * n_decode)
         if timed:
             e2.record()
+        step_no[0] += 1
 
     if args.calibrate:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -178,25 +199,23 @@ def main():
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()
+    ctx_first = duo.duo_cache_len(handle, 0) if not attn_prefill else n_prefill
     t_start = time.perf_counter()
     for _ in range(args.steps):
         one_step(True)
         torch.cuda.synchronize()
         pre_ms.append(e0.elapsed_time(e1))
         dec_ms.append(e1.elapsed_time(e2))
-        if n_decode:
-            # events bracket the n_decode back-to-back launches: average time per launch,
-            # launch gaps included (the kernel-only figure is in the rocprofv3 summary)
-            dec_kernel_ms.append(e1.elapsed_time(e2) / n_decode)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- algorithmic work
-    row_bytes = 2 * d
-    dec_bytes = []
-    for t in range(n_decode):
-        n_ctx = n_prefill + t + 1
+    row_bytes = d + 4 if kv_dtype else 2 * d
+    n_timed_tokens = n_decode if attn_prefill else n_decode * args.steps
+    dec_bytes = []           # per launch (one layer, one token, all sequences)
+    for t in range(n_timed_tokens):
+        n_ctx = ctx_first + t + 1
         dec_bytes.append(B * (n_ret * 2 * n_ctx * row_bytes + n_str * 2 * min(n_ctx, sink + recent) * row_bytes
                               + 2 * hq * d * 2))
     avg_dec_bytes = float(np.mean(dec_bytes)) if dec_bytes else 0.0
@@ -208,7 +227,9 @@ def main():
     pre_t = float(np.mean(pre_ms)) * 1e-3
     dec_t = float(np.mean(dec_ms)) * 1e-3
     us_per_token = dec_t / n_decode * 1e6 if n_decode else None
-    dec_call_us = float(np.mean(dec_kernel_ms)) * 1e3 if dec_kernel_ms else None
+    # events bracket the back-to-back launches of the phase: average time per launch, launch gaps
+    # included (the kernel-only figure is in the rocprofv3 summary)
+    dec_call_us = dec_t / (n_decode * n_layers) * 1e6 if n_decode else None
     dec_gbps = avg_dec_bytes / (dec_call_us * 1e-6) / 1e9 if dec_call_us else None
     pre_tflops = flops / pre_t / 1e12 if attn_prefill and pre_t > 0 else None
 
@@ -231,26 +252,7 @@ def main():
     # ---- the oracle on the host cores, bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline and n_decode:
-        import oracle
-        n_sample = 4 if n_prefill <= 40000 else 1
-        t_hist = n_prefill + n_sample
-        kh = synth.bf16_bits_to_f64(k_all[0, :t_hist].cpu().view(torch.int16).numpy().view(np.uint16))
-        vh = synth.bf16_bits_to_f64(v_all[0, :t_hist].cpu().view(torch.int16).numpy().view(np.uint16))
-        qh = [synth.bf16_bits_to_f64(q_dec[t][0, 0].cpu().view(torch.int16).numpy().view(np.uint16))
-              for t in range(n_sample)]
-        t0 = time.perf_counter()
-        for t in range(n_sample):
-            oracle.decode_step(qh[t], kh[:n_prefill + t + 1], vh[:n_prefill + t + 1], mask[0], sink, recent)
-        cpu_s = time.perf_counter() - t0
-        try:
-            from threadpoolctl import threadpool_info
-            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            threads = 1
-        cpu = {"value": round(cpu_s / n_sample * 1e6 * B, 1), "unit": "us/token", "cores": int(threads),
-               "kind": "oracle", "host_cores_available": len(os.sched_getaffinity(0)),
-               "sample": "%d decode tokens of sequence 0 at context %d (float64 numpy oracle), scaled by batch %d"
-                         % (n_sample, n_prefill, B)}
+        cpu = cpu_baseline(synth, args.seed, w, mask, n_prefill, B)
 
     result = {
         "metric": "decode_attn_us_per_token" if n_decode else "prefill_attn_tflops",
@@ -258,10 +260,11 @@ def main():
         "unit": "us/token" if n_decode else "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": False if n_decode else True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w["desc"], "name": args.workload, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": d,
-                   "retrieval_kv_heads": n_ret, "sink": sink, "recent": recent, "batch": B,
-                   "prefill_tokens": n_prefill, "chunk": chunk, "decode_steps": n_decode},
+        "dtype": "bf16" if not kv_dtype else "bf16 (fp8 e4m3 KV, fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": w["desc"], "name": args.workload, "n_layers": n_layers, "n_q_heads": hq,
+                   "n_kv_heads": hkv, "head_dim": d, "retrieval_kv_heads": n_ret, "sink": sink, "recent": recent,
+                   "batch": B, "prefill_tokens": n_prefill, "chunk": chunk, "decode_steps": n_decode,
+                   "cache_bytes": duo.duo_cache_bytes(handle)},
         "decode_hbm_GBps": round(dec_gbps, 1) if dec_gbps else None,
         "decode_call_us": round(dec_call_us, 2) if dec_call_us else None,
         "prefill_tflops": round(pre_tflops, 1) if pre_tflops else None,
@@ -271,6 +274,70 @@ def main():
     }
     duo.duo_cache_destroy(handle)
     print(json.dumps(result))
+
+
+def cpu_baseline(synth, seed, w, mask, n_ctx, batch):
+    """Time the float64 oracle (as it stands) on the host cores for a bounded sample of decode tokens:
+    whole tokens of sequence 0 for a one-layer workload; for the layer stacks one retrieval KV group of
+    layer 0, scaled by the number of retrieval KV groups of all layers (a streaming group costs
+    (sink + recent) / context of that, which is left out)."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    hq, hkv, d, sink, recent = w["hq"], w["hkv"], w["d"], w["sink"], w["recent"]
+    n_layers, fp8 = w.get("layers", 1), w.get("kv_dtype", 0) == 1
+    group = hq // hkv
+    n_sample = 4 if n_ctx <= 40000 else 1
+    t_hist = n_ctx + n_sample
+    whole = n_layers == 1
+    heads = list(range(hkv)) if whole else [int(np.flatnonzero(mask[0] == 1)[0])]
+
+    def history(tensor_id):
+        out = np.empty((t_hist, len(heads), d), dtype=np.uint16)
+        step = 1 << 15
+
+        def job(p0):
+            n = min(step, t_hist - p0)
+            out[p0:p0 + n] = synth.counter_bf16(seed, 0, tensor_id, 0, p0, n, hkv, d, heads=heads)
+
+        with ThreadPoolExecutor(8) as pool:
+            list(pool.map(job, range(0, t_hist, step)))
+        if not fp8:
+            return synth.bf16_bits_to_f64(out)
+        deq = np.empty(out.shape, dtype=np.float64)
+        qstep = 1 << 14
+
+        def qjob(p0):
+            codes, scales = oracle.quantize_rows(synth.bf16_bits_to_f32(out[p0:p0 + qstep]))
+            deq[p0:p0 + qstep] = oracle.dequantize_rows(codes, scales)
+
+        with ThreadPoolExecutor(8) as pool:
+            list(pool.map(qjob, range(0, t_hist, qstep)))
+        return deq
+
+    kh, vh = history(synth.TENSOR_K), history(synth.TENSOR_V)
+    q_heads = slice(0, hq) if whole else slice(heads[0] * group, (heads[0] + 1) * group)
+    qh = synth.bf16_bits_to_f64(synth.counter_bf16(seed, 0, synth.TENSOR_Q, 0, n_ctx, n_sample, hq, d))[:, q_heads]
+    sub_mask = mask[0] if whole else np.array([1], dtype=np.uint8)
+    t0 = time.perf_counter()
+    for t in range(n_sample):
+        oracle.decode_step(qh[t], kh[:n_ctx + t + 1], vh[:n_ctx + t + 1], sub_mask, sink, recent)
+    cpu_s = (time.perf_counter() - t0) / n_sample
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    if whole:
+        value, what = cpu_s * batch, "%d decode tokens of sequence 0 at context %d, scaled by batch %d" % (
+            n_sample, n_ctx, batch)
+    else:
+        n_groups = int(mask.sum())
+        value, what = cpu_s * n_groups * batch, ("one retrieval KV group (%d query heads) of layer 0 for one token at "
+                                                 "context %d, scaled by the %d retrieval KV groups of the %d layers"
+                                                 % (group, n_ctx, n_groups, n_layers))
+    return {"value": round(value * 1e6, 1), "unit": "us/token", "cores": int(threads), "kind": "oracle",
+            "host_cores_available": len(os.sched_getaffinity(0)),
+            "sample": what + " (float64 numpy oracle; inputs regenerated on the CPU, not timed)"}
 
 
 if __name__ == "__main__":

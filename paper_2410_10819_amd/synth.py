@@ -68,16 +68,28 @@ def stream_key(seed: int, layer: int, tensor: int, batch_idx: int) -> int:
     return int(b[0])
 
 
-def counter_bf16(seed, layer, tensor, batch_idx, pos_start, n_pos, n_heads, head_dim) -> np.ndarray:
-    """bf16 bits [n_pos, n_heads, head_dim] of positions pos_start .. pos_start+n_pos-1."""
+def counter_bf16(seed, layer, tensor, batch_idx, pos_start, n_pos, n_heads, head_dim, heads=None) -> np.ndarray:
+    """bf16 bits [n_pos, n_heads, head_dim] of positions pos_start .. pos_start+n_pos-1.
+
+    With `heads` (a list of head indices) only those heads are produced:
+    [n_pos, len(heads), head_dim], the same bits the full tensor holds there.
+    """
     key = np.uint64(stream_key(seed, layer, tensor, batch_idx))
-    per_pos = n_heads * head_dim
-    idx = (np.arange(n_pos * per_pos, dtype=np.uint64)
-           + np.uint64(pos_start) * np.uint64(per_pos))
-    with np.errstate(over="ignore"):
-        h = _mix(key ^ (idx * _GOLDEN))
     tab = normal_table_bf16()
-    return tab[(h >> np.uint64(48)).astype(np.int64)].reshape(n_pos, n_heads, head_dim)
+    head_list = np.arange(n_heads, dtype=np.uint64) if heads is None else np.asarray(heads, dtype=np.uint64)
+    # counter of (pos, head, d) = (pos * n_heads + head) * head_dim + d
+    inner = (head_list[:, None] * np.uint64(head_dim) + np.arange(head_dim, dtype=np.uint64)[None, :]).reshape(-1)
+    out = np.empty((n_pos, inner.size), dtype=np.uint16)
+    per_pos = np.uint64(n_heads * head_dim)
+    block = max(1, (1 << 17) // max(inner.size, 1))        # keep the temporaries cache-sized
+    for p0 in range(0, n_pos, block):
+        p1 = min(n_pos, p0 + block)
+        pos = np.arange(pos_start + p0, pos_start + p1, dtype=np.uint64)
+        with np.errstate(over="ignore"):
+            idx = pos[:, None] * per_pos + inner[None, :]
+            h = _mix(key ^ (idx * _GOLDEN))
+        out[p0:p1] = tab[(h >> np.uint64(48)).astype(np.int64)]
+    return out.reshape(n_pos, head_list.size, head_dim)
 
 
 def counter_bf16_batch(seed, layer, tensor, batch, pos_start, n_pos, n_heads, head_dim) -> np.ndarray:

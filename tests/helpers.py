@@ -117,3 +117,64 @@ def oracle_rows(cfg, q_bits, k_bits, v_bits, positions, batch_idx=0):
     qf = synth.bf16_bits_to_f64(q_bits[batch_idx][np.asarray(positions)])
     scale = cfg.get("scale", 0.0) or None
     return oracle.attention_rows(qf, kf, vf, positions, cfg["mask"], cfg["sink"], cfg["recent"], scale)
+
+
+# ---- full-size cases: inputs generated on the device, the CPU regenerates the slices it checks
+
+def device_table():
+    import torch
+    return torch.from_numpy(synth.normal_table_bf16().view(np.int16)).cuda()
+
+
+def device_fill(table, seed, layer, tensor, batch, pos_start, n_pos, heads, d):
+    """bf16 [batch, n_pos, heads, d] on the device: the counter generator's bits."""
+    import torch
+    from paper_2410_10819_amd import binding as duo
+    t = torch.empty((batch, n_pos, heads, d), dtype=torch.bfloat16, device="cuda")
+    for b in range(batch):
+        duo.duo_synth_fill_bf16(t[b], table, synth.stream_key(seed, layer, tensor, b), pos_start, n_pos, heads, d)
+    return t
+
+
+def fill_cache_by_append(duo, handle, table, seed, layer, batch, hkv, d, n_tokens, chunk=65536):
+    """Append positions 0 .. n_tokens-1 of the seeded K/V streams of `layer` to the cache."""
+    for p in range(0, n_tokens, chunk):
+        n = min(chunk, n_tokens - p)
+        k = device_fill(table, seed, layer, synth.TENSOR_K, batch, p, n, hkv, d)
+        v = device_fill(table, seed, layer, synth.TENSOR_V, batch, p, n, hkv, d)
+        duo.duo_kv_append(handle, layer, k, v, n)
+
+
+def cpu_history_bits(seed, layer, tensor, batch_idx, n_tokens, n_heads, d, heads=None, workers=8):
+    """bf16 bits [n_tokens, len(heads), d] of one sequence, regenerated on the CPU in parallel blocks."""
+    sel = list(range(n_heads)) if heads is None else list(heads)
+    out = np.empty((n_tokens, len(sel), d), dtype=np.uint16)
+    step = 1 << 15
+
+    def job(p0):
+        n = min(step, n_tokens - p0)
+        out[p0:p0 + n] = synth.counter_bf16(seed, layer, tensor, batch_idx, p0, n, n_heads, d, heads=sel)
+
+    synth.normal_table_bf16()
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(workers) as pool:
+        list(pool.map(job, range(0, n_tokens, step)))
+    return out
+
+
+def oracle_history_f64(bits, fp8, workers=8):
+    """float64 history the oracle attends over: the bf16 values, or their fp8 round trip through the
+    oracle's codec (applied block by block; each row is coded independently)."""
+    if not fp8:
+        return synth.bf16_bits_to_f64(bits)
+    out = np.empty(bits.shape, dtype=np.float64)
+    step = 1 << 14
+
+    def job(p0):
+        codes, scales = oracle.quantize_rows(synth.bf16_bits_to_f32(bits[p0:p0 + step]))
+        out[p0:p0 + step] = oracle.dequantize_rows(codes, scales)
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(workers) as pool:
+        list(pool.map(job, range(0, bits.shape[0], step)))
+    return out

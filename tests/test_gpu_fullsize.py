@@ -1,0 +1,181 @@
+"""The benchmark configurations at their full sizes, in the launch configuration bench.py times.
+
+The float64 oracle cannot produce whole output tensors at these sizes in reasonable time, so each
+case compares sampled outputs it can compute one by one: for pre-filling a seeded sample of query
+rows per chunk (always the chunk's first and last row, and the rows at positions sink,
+sink + recent - 1 and sink + recent where the Lambda mask changes shape), all heads; for decoding
+whole tokens (all heads, or one retrieval and one streaming KV group per checked layer at the
+million-token sizes).  Inputs come from the counter generator: the device fills the tensors, the
+CPU regenerates exactly the same bits for the oracle.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2410_10819_amd import binding as duo
+from paper_2410_10819_amd import synth
+from helpers import (ATOL_LSE, assert_close, cpu_history_bits, device_fill, device_table, fill_cache_by_append,
+                     from_dev_bits, oracle_history_f64)
+
+pytestmark = pytest.mark.gpu
+
+SINK, RECENT = 64, 256
+
+
+def _sample_positions(rng, pos0, n, extra):
+    fixed = [pos0, pos0 + n - 1] + [p for p in (SINK, SINK + RECENT - 1, SINK + RECENT) if pos0 <= p < pos0 + n]
+    rand = rng.integers(pos0, pos0 + n, size=extra).tolist()
+    return sorted(set(fixed + rand))
+
+
+def _oracle_check(q_rows_bits, k_hist, v_hist, positions, mask, got_bits, got_lse, what):
+    """q_rows_bits [n, Hq, D] bits of the sampled queries; got_bits same shape; got_lse [Hq, n] or None."""
+    qf = synth.bf16_bits_to_f64(q_rows_bits)
+    want_o, want_lse = oracle.attention_rows(qf, k_hist, v_hist, positions, mask, SINK, RECENT)
+    stats = assert_close(synth.bf16_bits_to_f64(got_bits), want_o, what)
+    if got_lse is not None:
+        assert np.abs(got_lse - want_lse).max() <= ATOL_LSE, what
+    return stats
+
+
+def _prefill_and_decode(hq, hkv, d, ratio, n_prefill, chunk, n_decode, n_rand, seed):
+    import torch
+    total = n_prefill + n_decode
+    mask = synth.retrieval_mask(seed, 1, hkv, ratio)[0]
+    table = device_table()
+    q = device_fill(table, seed, 0, synth.TENSOR_Q, 1, 0, total, hq, d)
+    k = device_fill(table, seed, 0, synth.TENSOR_K, 1, 0, total, hkv, d)
+    v = device_fill(table, seed, 0, synth.TENSOR_V, 1, 0, total, hkv, d)
+    out = torch.empty_like(q)
+    lse = torch.empty((1, hq, total), dtype=torch.float32, device="cuda")
+    handle = duo.duo_cache_create(1, 1, hq, hkv, d, SINK, RECENT, total, mask[None])
+    rng = np.random.default_rng(seed + 1000)
+    positions = []
+    try:
+        for p in range(0, n_prefill, chunk):
+            lse_c = torch.empty((1, hq, chunk), dtype=torch.float32, device="cuda")
+            duo.duo_attn_prefill(handle, 0, q[:, p:p + chunk], k[:, p:p + chunk], v[:, p:p + chunk], chunk,
+                                 out[:, p:p + chunk], lse=lse_c)
+            duo.duo_kv_append(handle, 0, k[:, p:p + chunk], v[:, p:p + chunk], chunk)
+            lse[:, :, p:p + chunk] = lse_c
+            positions += _sample_positions(rng, p, chunk, n_rand)
+        for t in range(n_prefill, total):
+            lse_t = torch.empty((1, hq), dtype=torch.float32, device="cuda")
+            duo.duo_decode_step(handle, 0, q[:, t:t + 1], k[:, t:t + 1], v[:, t:t + 1], out[:, t:t + 1], lse=lse_t)
+            lse[:, :, t] = lse_t
+        if n_decode:
+            positions += sorted(set([n_prefill, total - 1] + rng.integers(n_prefill, total, size=2).tolist()))
+        torch.cuda.synchronize()
+        assert duo.duo_cache_len(handle, 0) == total
+    finally:
+        duo.duo_cache_destroy(handle)
+    positions = np.array(positions)
+    k_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_K, 0, total, hkv, d))
+    v_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_V, 0, total, hkv, d))
+    # the device generator and the CPU generator agree on the bits (spot check on the sampled rows)
+    idx = torch.from_numpy(positions).cuda()
+    assert np.array_equal(from_dev_bits(k[0, idx]), cpu_history_bits(seed, 0, synth.TENSOR_K, 0, total, hkv, d)[positions])
+    q_rows = from_dev_bits(q[0, idx])
+    got = from_dev_bits(out[0, idx])
+    got_lse = lse[0][:, idx].cpu().numpy().astype(np.float64)
+    return _oracle_check(q_rows, k_hist, v_hist, positions, mask, got, got_lse, "%d positions" % len(positions))
+
+
+def test_llama2_7b_shape_32k_prefill_4k_chunks_and_256_decode_steps():
+    # 32 MHA heads x 128, 8 retrieval heads, prefill 32768 in 4096-token chunks, 256 decode steps
+    _prefill_and_decode(32, 32, 128, 0.25, 32768, 4096, 256, n_rand=3, seed=0)
+
+
+def test_llama3_8b_shape_128k_prefill_32k_chunks():
+    # 32 query / 8 KV heads x 128, 4 retrieval KV heads, prefill 131072 in 32768-token chunks
+    _prefill_and_decode(32, 8, 128, 0.5, 131072, 32768, 0, n_rand=1, seed=0)
+
+
+@pytest.mark.parametrize("batch", [1, 4, 16])
+def test_llama3_8b_shape_decode_at_128k_context(batch):
+    import torch
+    hq, hkv, d, n_ctx, seed = 32, 8, 128, 131072, 3
+    mask = synth.retrieval_mask(seed, 1, hkv, 0.5)[0]
+    table = device_table()
+    handle = duo.duo_cache_create(1, batch, hq, hkv, d, SINK, RECENT, n_ctx + 2, mask[None])
+    try:
+        fill_cache_by_append(duo, handle, table, seed, 0, batch, hkv, d, n_ctx, chunk=32768)
+        outs, lses = [], []
+        for t in range(n_ctx, n_ctx + 2):
+            q = device_fill(table, seed, 0, synth.TENSOR_Q, batch, t, 1, hq, d)
+            k = device_fill(table, seed, 0, synth.TENSOR_K, batch, t, 1, hkv, d)
+            v = device_fill(table, seed, 0, synth.TENSOR_V, batch, t, 1, hkv, d)
+            o = torch.empty_like(q)
+            l = torch.empty((batch, hq), dtype=torch.float32, device="cuda")
+            duo.duo_decode_step(handle, 0, q, k, v, o, lse=l)
+            outs.append(from_dev_bits(o)); lses.append(l.cpu().numpy().astype(np.float64))
+        assert duo.duo_cache_len(handle, 0) == n_ctx + 2
+    finally:
+        duo.duo_cache_destroy(handle)
+    for b in sorted({0, batch - 1}):
+        k_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_K, b, n_ctx + 2, hkv, d))
+        v_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_V, b, n_ctx + 2, hkv, d))
+        for i, t in enumerate((n_ctx, n_ctx + 1)):
+            q_bits = synth.counter_bf16(seed, 0, synth.TENSOR_Q, b, t, 1, hq, d)
+            _oracle_check(q_bits, k_hist, v_hist, [t], mask, outs[i][b], lses[i][b][:, None],
+                          "batch %d of %d, token %d" % (b, batch, t))
+
+
+def _long_context_stack(n_ctx, kv_dtype, n_layers, check_layers, seed):
+    """Decode one token through a stack of layers whose caches were filled by append alone; the oracle
+    checks one retrieval and one streaming KV group of each layer in check_layers."""
+    import torch
+    hq, hkv, d, group = 32, 8, 128, 4
+    mask = synth.retrieval_mask(seed, n_layers, hkv, 0.5)
+    table = device_table()
+    handle = duo.duo_cache_create(n_layers, 1, hq, hkv, d, SINK, RECENT, n_ctx + 1, mask, kv_dtype)
+    outs, lses = {}, {}
+    try:
+        for layer in range(n_layers):
+            fill_cache_by_append(duo, handle, table, seed, layer, 1, hkv, d, n_ctx, chunk=1 << 17)
+        for layer in range(n_layers):
+            q = device_fill(table, seed, layer, synth.TENSOR_Q, 1, n_ctx, 1, hq, d)
+            k = device_fill(table, seed, layer, synth.TENSOR_K, 1, n_ctx, 1, hkv, d)
+            v = device_fill(table, seed, layer, synth.TENSOR_V, 1, n_ctx, 1, hkv, d)
+            o = torch.empty_like(q)
+            l = torch.empty((1, hq), dtype=torch.float32, device="cuda")
+            duo.duo_decode_step(handle, layer, q, k, v, o, lse=l)
+            if layer in check_layers:
+                outs[layer] = from_dev_bits(o)[0, 0]
+                lses[layer] = l.cpu().numpy().astype(np.float64)[0]
+        torch.cuda.synchronize()
+        assert all(duo.duo_cache_len(handle, layer) == n_ctx + 1 for layer in range(n_layers))
+    finally:
+        duo.duo_cache_destroy(handle)
+    for layer in check_layers:
+        ret_head = int(np.flatnonzero(mask[layer] == 1)[0])
+        str_head = int(np.flatnonzero(mask[layer] == 0)[-1])
+        for kvh in (ret_head, str_head):
+            if kvh == ret_head:
+                kb = cpu_history_bits(seed, layer, synth.TENSOR_K, 0, n_ctx + 1, hkv, d, heads=[kvh])
+                vb = cpu_history_bits(seed, layer, synth.TENSOR_V, 0, n_ctx + 1, hkv, d, heads=[kvh])
+                k_hist, v_hist = oracle_history_f64(kb, kv_dtype == 1), oracle_history_f64(vb, kv_dtype == 1)
+                del kb, vb
+            else:
+                # the oracle masks every other row of a streaming head, so only the rows it can see are
+                # regenerated (the device cache was filled with the real data of every position)
+                k_hist = np.zeros((n_ctx + 1, 1, d))
+                v_hist = np.zeros((n_ctx + 1, 1, d))
+                for p0, n in ((0, SINK), (n_ctx + 1 - RECENT, RECENT)):
+                    kb = synth.counter_bf16(seed, layer, synth.TENSOR_K, 0, p0, n, hkv, d, heads=[kvh])
+                    vb = synth.counter_bf16(seed, layer, synth.TENSOR_V, 0, p0, n, hkv, d, heads=[kvh])
+                    k_hist[p0:p0 + n] = oracle_history_f64(kb, kv_dtype == 1)
+                    v_hist[p0:p0 + n] = oracle_history_f64(vb, kv_dtype == 1)
+            heads = slice(kvh * group, (kvh + 1) * group)
+            q_bits = synth.counter_bf16(seed, layer, synth.TENSOR_Q, 0, n_ctx, 1, hq, d)[:, heads]
+            _oracle_check(q_bits, k_hist, v_hist, [n_ctx], mask[layer][kvh:kvh + 1], outs[layer][None, heads],
+                          lses[layer][heads][:, None], "layer %d kv head %d" % (layer, kvh))
+            del k_hist, v_hist
+
+
+def test_llama3_8b_shape_decode_at_1m_context_32_layers_bf16():
+    _long_context_stack(1 << 20, duo.DUO_KV_BF16, 32, check_layers=(0, 31), seed=4)
+
+
+def test_llama3_8b_shape_decode_at_3300000_context_32_layers_fp8():
+    _long_context_stack(3300000, duo.DUO_KV_FP8_E4M3, 32, check_layers=(17,), seed=5)
