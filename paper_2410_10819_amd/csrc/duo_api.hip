@@ -84,16 +84,20 @@ int check_params(const duo_cache* c, int layer, const duo_call_params_t* p) {
   return DUO_OK;
 }
 
-// Splits per retrieval head: enough work items to fill the chip a few times
-// over while keeping at least kMinKeysPerSplit keys in each.
+// Splits per retrieval head.  A workgroup with its two register buffers keeps
+// enough bytes in flight for its compute unit, so the aim is one resident
+// workgroup per compute unit (two when the per-row arithmetic of a query group is
+// heavy) with streaming heads counted in, and at least kMinKeysPerSplit keys each.
 int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
   if (c->user_splits > 0) return c->user_splits < c->max_splits ? c->user_splits : c->max_splits;
   const int64_t kMinKeysPerSplit = 256;
-  const int64_t target_items = 256;
-  int64_t heads = (int64_t)L.view.n_ret * c->cfg.batch;
+  const int64_t heads = (int64_t)L.view.n_ret * c->cfg.batch;
   if (heads == 0) return 1;
-  int64_t s = (target_items + heads - 1) / heads;
-  int64_t by_len = keys / kMinKeysPerSplit;
+  const int64_t slots = (L.view.group >= 2 || c->cfg.kv_dtype == DUO_KV_FP8_E4M3) ? 512 : 256;
+  int64_t budget = slots - (int64_t)L.view.n_str * c->cfg.batch;
+  if (budget < slots / 2) budget = slots / 2;
+  int64_t s = budget / heads;
+  const int64_t by_len = keys / kMinKeysPerSplit;
   if (s > by_len) s = by_len;
   if (s > c->max_splits) s = c->max_splits;
   if (s < 1) s = 1;

@@ -37,6 +37,13 @@ __device__ inline uint16_t f32_to_bf16(float f) {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Load of a table entry whose address is the same for the whole workgroup and
+// whose memory no kernel writes: through the constant address space, i.e. the
+// scalar unit, so the dependent address arithmetic does not wait for a vector load.
+__device__ inline int uniform_load(const int32_t* p) {
+  return *(const __attribute__((address_space(4))) int32_t*)(uintptr_t)p;
+}
+
 // Device-scope accesses for data exchanged between workgroups inside one launch.
 __device__ inline void coherent_store(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -114,10 +121,12 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   constexpr int LPR = D / EPL;         // lanes per row
   constexpr int RPL = 64 / LPR;        // rows per wavefront load
   constexpr int RPB = 4 * RPL;         // rows per block iteration (4 wavefronts)
-#ifndef DUO_EXP_U
-#define DUO_EXP_U 4
+#ifdef DUO_EXP_U
+  constexpr int U = DUO_EXP_U;
+#else
+  // row iterations per register buffer: as many as fit beside the per-head state
+  constexpr int U = (FP8 && G == 2) ? 2 : 4;
 #endif
-  constexpr int U = DUO_EXP_U;         // row iterations per register buffer
   constexpr int STEP = RPB * U;        // rows per buffer
   const LayerView& lv = a.lv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -135,7 +144,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     const int slot = blockIdx.x / a.splits;
     split = blockIdx.x % a.splits;
     nsplit = a.splits;
-    kvh = lv.ret_heads[slot];
+    kvh = uniform_load(lv.ret_heads + slot);
     int64_t chunk = (a.cache_len + nsplit - 1) / nsplit;
     chunk = (chunk + RPB - 1) / RPB * RPB;
     j0 = (int64_t)split * chunk;
@@ -150,7 +159,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   } else {
     const int slot = blockIdx.x - n_ret_items;
     nsplit = 1;
-    kvh = lv.str_heads[slot];
+    kvh = uniform_load(lv.str_heads + slot);
     const int64_t cap = (int64_t)lv.sink + lv.recent;
     j0 = 0;
     j1 = streaming_rows(a.cache_len, lv.sink, lv.recent);
@@ -165,16 +174,58 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     if (FP8) { ksbase = lv.ks_str + head_row0; vsbase = lv.vs_str + head_row0; }
   }
 
+  struct Buf { uint4 k[U], v[U]; float ks[U], vs[U]; };
+  const int row_in_block = wave * RPL + grp;
+  // Loads past the item's end are redirected to its last row (row 0 of the head's
+  // cache for an empty item: allocated memory whose value is then ignored).
+  const int64_t last_row = j1 > 0 ? j1 - 1 : 0;
+  auto issue = [&](Buf& buf, int64_t base) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = base + u * RPB + row_in_block;
+      const int64_t rc = r < j1 ? r : last_row;
+      buf.k[u] = *(const uint4*)(kbase + rc * lv.row_bytes + sub * 16);
+      buf.v[u] = *(const uint4*)(vbase + rc * lv.row_bytes + sub * 16);
+      if constexpr (FP8) { buf.ks[u] = ksbase[rc]; buf.vs[u] = vsbase[rc]; }
+    }
+  };
+  // Raw query pieces and the new token's pieces first (they are waited for first),
+  // then the first K/V rows; the barrier keeps that issue order.
+  uint4 q_raw[G][EPL / 8];
+  {
+    const uint4* qp = (const uint4*)((const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G) * D + sub * EPL);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int i = 0; i < EPL / 8; ++i) q_raw[g][i] = qp[g * (D / 8) + i];
+  }
+  uint4 new_k[EPL / 8], new_v[EPL / 8];   // the new token's piece: EPL bf16 values
+  if (with_new) {
+    const uint4* kin = (const uint4*)((const uint16_t*)a.k_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * EPL);
+    const uint4* vin = (const uint4*)((const uint16_t*)a.v_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * EPL);
+#pragma unroll
+    for (int i = 0; i < EPL / 8; ++i) { new_k[i] = kin[i]; new_v[i] = vin[i]; }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  Buf buf_a;
+  issue(buf_a, j0);
+  __builtin_amdgcn_sched_barrier(0);
+
   // Query pieces of the group's heads, pre-multiplied by scale * log2(e).
   float q[G][EPL];
   {
     const float c = lv.scale * kLog2e;
-    const uint16_t* qp = (const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G) * D + sub * EPL;
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) q[g][i] = __uint_as_float((uint32_t)qp[g * D + i] << 16) * c;
+      for (int i = 0; i < EPL / 8; ++i) {
+        float f[8];
+        Piece<false>::widen(q_raw[g][i], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[g][8 * i + e] = f[e] * c;
+      }
   }
+  __builtin_amdgcn_sched_barrier(0);
   float m[G], l[G], o[G][EPL];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -183,18 +234,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     for (int i = 0; i < EPL; ++i) o[g][i] = 0.f;
   }
 
-  struct Buf { uint4 k[U], v[U]; float ks[U], vs[U]; };
-  const int row_in_block = wave * RPL + grp;
-  auto issue = [&](Buf& buf, int64_t base) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t r = base + u * RPB + row_in_block;
-      const int64_t rc = r < j1 ? r : j1 - 1;
-      buf.k[u] = *(const uint4*)(kbase + rc * lv.row_bytes + sub * 16);
-      buf.v[u] = *(const uint4*)(vbase + rc * lv.row_bytes + sub * 16);
-      if constexpr (FP8) { buf.ks[u] = ksbase[rc]; buf.vs[u] = vsbase[rc]; }
-    }
-  };
   auto consume = [&](const Buf& buf, int64_t base) {
     float s[U][G];
 #pragma unroll
@@ -242,37 +281,70 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     }
   };
 
-  for (int64_t base = j0; base < j1; base += STEP) {
-    Buf buf;
-    issue(buf, base);
-    consume(buf, base);
+  // Two register buffers: the loads of the next STEP rows are in flight while the
+  // current buffer is consumed.  Inside the loop every issue is unconditional (a
+  // conditional one would make the compiler's wait counts assume the shorter queue
+  // and drain it); the scheduling barriers keep the loads from being sunk below the
+  // arithmetic.  Nothing is loaded past the item's last row.  The variants with the
+  // most per-head state have no registers for a second buffer.
+  constexpr bool kTwoBuffers = !((FP8 && G >= 4) || G >= 8);
+  if (j0 < j1) {
+    int64_t base = j0;
+    if constexpr (kTwoBuffers) {
+      Buf buf_b;
+      while (base + 2 * STEP < j1) {
+        issue(buf_b, base + STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(buf_a, base);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(buf_a, base + 2 * STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(buf_b, base + STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        base += 2 * STEP;
+      }
+      if (base + STEP < j1) {
+        issue(buf_b, base + STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(buf_a, base);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(buf_b, base + STEP);
+      } else {
+        consume(buf_a, base);
+      }
+    } else {
+      consume(buf_a, base);
+      for (base += STEP; base < j1; base += STEP) {
+        issue(buf_a, base);
+        consume(buf_a, base);
+      }
+    }
   }
 
   // The new token, handled by row group 0 of wavefront 0 of the item that owns it;
   // with a.commit its rows are also written into the cache.
   if (with_new && wave == 0 && grp == 0) {
-    const uint16_t* kin = (const uint16_t*)a.k_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * EPL;
-    const uint16_t* vin = (const uint16_t*)a.v_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * EPL;
     float kf[EPL], vf[EPL];
     float ksc = 1.f, vsc = 1.f;
     if constexpr (!FP8) {
-      const uint4 kc = *(const uint4*)kin;
-      const uint4 vc = *(const uint4*)vin;
-      Piece<false>::widen(kc, kf);
-      Piece<false>::widen(vc, vf);
+      Piece<false>::widen(new_k[0], kf);
+      Piece<false>::widen(new_v[0], vf);
       if (a.commit) {
-        *(uint4*)(kbase + new_row * lv.row_bytes + sub * 16) = kc;
-        *(uint4*)(vbase + new_row * lv.row_bytes + sub * 16) = vc;
+        *(uint4*)(kbase + new_row * lv.row_bytes + sub * 16) = new_k[0];
+        *(uint4*)(vbase + new_row * lv.row_bytes + sub * 16) = new_v[0];
       }
     } else {
       // quantise exactly as the append kernel does, then attend to the dequantised row
       float kmax = 0.f, vmax = 0.f;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        kf[i] = __uint_as_float((uint32_t)kin[i] << 16);
-        vf[i] = __uint_as_float((uint32_t)vin[i] << 16);
-        kmax = fmaxf(kmax, fabsf(kf[i]));
-        vmax = fmaxf(vmax, fabsf(vf[i]));
+      for (int i = 0; i < 2; ++i) {
+        float f[8];
+        Piece<false>::widen(new_k[i], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { kf[8 * i + e] = f[e]; kmax = fmaxf(kmax, fabsf(f[e])); }
+        Piece<false>::widen(new_v[i], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { vf[8 * i + e] = f[e]; vmax = fmaxf(vmax, fabsf(f[e])); }
       }
       kmax = group_max<LPR>(kmax);
       vmax = group_max<LPR>(vmax);
@@ -330,8 +402,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   constexpr int kSmO = 4 * G * D > 1024 ? 4 * G * D : 1024;
   __shared__ float sm_o[kSmO];   // [wave][g][d] during the wavefront merge, [part][d] in the split merge
   __shared__ float sm_m[4][G], sm_l[4][G];
-  __shared__ float sm_w[kMaxDecodeSplits];
-  __shared__ float sm_red[8];
+  __shared__ float sm_m2[16], sm_l2[16];   // per merge slot, in the split merge
   __shared__ int sm_last;
   if (grp == 0) {
 #pragma unroll
@@ -384,52 +455,67 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   if (!sm_last) return;
   // Acquire: drop any stale cached copies of the partials before reading them.
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  constexpr int TPR = D / 4;        // threads per partial row (one float4 each)
-  constexpr int NP = 256 / TPR;     // partial rows in flight
-  const int dq = tid % TPR, part = tid / TPR;
-  float* flat = sm_o;
-  for (int g = 0; g < G; ++g) {
-    const int h = kvh * G + g;
+  // All heads of the group at once, one memory round trip: the 256 threads form
+  // SLOTS rows of TPR threads (one float4 of a partial row each); head g owns NP
+  // consecutive slots, slot `part` of a head sums the partials part, part + NP, ...
+  // in that order with a running maximum, and the NP slot results are merged
+  // through LDS in slot order - a fixed order, so the result is deterministic.
+  constexpr int TPR = D / 4;
+  constexpr int SLOTS = 256 / TPR;
+  static_assert(SLOTS % G == 0, "group size must divide the merge slots");
+  constexpr int NP = SLOTS / G;
+  const int dq = tid % TPR, slot_id = tid / TPR;
+  const int mg = slot_id / NP, part = slot_id % NP;
+  {
+    const int h = kvh * G + mg;
     const int64_t p0 = ((int64_t)b * lv.n_q_heads + h) * nsplit;
-    // weights of the partials: w_s = 2^(m_s - M), L = sum w_s l_s
     const float2* ml = (const float2*)a.part_ml + p0;
-    float2 mine = make_float2(-INFINITY, 0.f);
-    if (tid < nsplit) mine = ml[tid];
-    float mloc = mine.x;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, off));
-    __syncthreads();
-    if (lane == 0) sm_red[wave] = mloc;
-    __syncthreads();
-    const float mn = fmaxf(fmaxf(sm_red[0], sm_red[1]), fmaxf(sm_red[2], sm_red[3]));
-    const float wgt = fast_exp2(mine.x - mn);
-    if (tid < nsplit) sm_w[tid] = wgt;
-    float lloc = wgt * mine.y;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) lloc += __shfl_xor(lloc, off);
-    if (lane == 0) sm_red[4 + wave] = lloc;
-    __syncthreads();
-    const float ls = (sm_red[4] + sm_red[5]) + (sm_red[6] + sm_red[7]);
-    // output: thread (part, dq) sums the partials s = part, part + NP, ... in order
     const float4* po = (const float4*)(a.part_o + p0 * D) + dq;
+    float mr = -INFINITY, lr = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = part; s < nsplit; s += NP) {
-      const float4 x = po[(int64_t)s * TPR];
-      const float w = sm_w[s];
-      acc.x = fmaf(w, x.x, acc.x); acc.y = fmaf(w, x.y, acc.y);
-      acc.z = fmaf(w, x.z, acc.z); acc.w = fmaf(w, x.w, acc.w);
-    }
-    __syncthreads();
-    *(float4*)(flat + part * D + 4 * dq) = acc;   // NP * D = 1024 floats
-    __syncthreads();
-    if (tid < D) {
-      float tot = 0.f;
+    constexpr int B4 = 4;   // partial rows fetched together
+    for (int s0 = part; s0 < nsplit; s0 += NP * B4) {
+      float2 mlv[B4];
+      float4 x[B4];
 #pragma unroll
-      for (int pp = 0; pp < NP; ++pp) tot += flat[pp * D + tid];
-      ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + h) * D + tid] = f32_to_bf16(tot / ls);
-      if (a.lse && tid == 0) a.lse[(int64_t)b * lv.n_q_heads + h] = (mn + log2f(ls)) * kLn2;
+      for (int j = 0; j < B4; ++j) {
+        const int sidx = s0 + j * NP;
+        const int sc = sidx < nsplit ? sidx : nsplit - 1;
+        mlv[j] = ml[sc];
+        x[j] = po[(int64_t)sc * TPR];
+        if (sidx >= nsplit) mlv[j] = make_float2(-INFINITY, 0.f);
+      }
+#pragma unroll
+      for (int j = 0; j < B4; ++j) {
+        const float mn = fmaxf(mr, mlv[j].x);
+        const float mu = mn == -INFINITY ? 0.f : mn;
+        const float a1 = fast_exp2(mr - mu), a2 = fast_exp2(mlv[j].x - mu);
+        lr = lr * a1 + mlv[j].y * a2;
+        acc.x = acc.x * a1 + x[j].x * a2; acc.y = acc.y * a1 + x[j].y * a2;
+        acc.z = acc.z * a1 + x[j].z * a2; acc.w = acc.w * a1 + x[j].w * a2;
+        mr = mn;
+      }
     }
-    __syncthreads();
+    __syncthreads();   // sm_o / sm_m / sm_l are free again
+    *(float4*)(sm_o + slot_id * D + 4 * dq) = acc;
+    if (dq == 0) { sm_m2[slot_id] = mr; sm_l2[slot_id] = lr; }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * D; idx += 256) {
+    const int g = idx / D, d = idx % D;
+    float mn = -INFINITY;
+#pragma unroll
+    for (int pp = 0; pp < NP; ++pp) mn = fmaxf(mn, sm_m2[g * NP + pp]);
+    float tot = 0.f, ls = 0.f;
+#pragma unroll
+    for (int pp = 0; pp < NP; ++pp) {
+      const float wgt = fast_exp2(sm_m2[g * NP + pp] - mn);
+      tot += wgt * sm_o[(g * NP + pp) * D + d];
+      ls += wgt * sm_l2[g * NP + pp];
+    }
+    const int h = kvh * G + g;
+    ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + h) * D + d] = f32_to_bf16(tot / ls);
+    if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + h] = (mn + log2f(ls)) * kLn2;
   }
 }
 
