@@ -62,7 +62,7 @@ typedef enum {
 typedef struct {
   int32_t n_layers;              /* >= 1 */
   int32_t batch;                 /* >= 1; sequences advance in lock-step */
-  int32_t n_q_heads;             /* multiple of n_kv_heads, group size <= 8 */
+  int32_t n_q_heads;             /* multiple of n_kv_heads, group size 1, 2, 4 or 8 */
   int32_t n_kv_heads;            /* >= 1 */
   int32_t head_dim;              /* 64 or 128 */
   int32_t sink;                  /* >= 0 attention-sink tokens kept by streaming heads */
@@ -145,9 +145,14 @@ int duo_cache_export(duo_cache_t* cache, int layer, int batch_idx, int kv_head,
                      int64_t* positions_out, int64_t capacity, int64_t* count_out,
                      void* stream);
 
-/* Tuning knob: number of key splits per retrieval head in decode (0 = automatic).
- * Results do not depend on it beyond floating-point rounding. */
+/* Tuning knob: number of workgroups per retrieval (sequence, KV head) that share its keys in
+ * decode (0 = automatic).  Results do not depend on it beyond floating-point rounding. */
 int duo_set_decode_splits(duo_cache_t* cache, int splits);
+
+/* Tuning knob: which decode kernel serves the handle.  0 = automatic (the vector-unit kernel
+ * for one query head per KV head on a bf16 cache, the matrix-core kernel for query groups and
+ * fp8 caches), 1 = always the matrix-core kernel.  Same results up to rounding. */
+int duo_set_decode_kernel(duo_cache_t* cache, int kernel);
 
 /* Thread-local description of the last error returned on this thread. */
 const char* duo_last_error(void);

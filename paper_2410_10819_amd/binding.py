@@ -61,6 +61,7 @@ def load() -> ctypes.CDLL:
     lib.duo_cache_bytes.argtypes = [vp]
     lib.duo_cache_bytes.restype = i64
     lib.duo_set_decode_splits.argtypes = [vp, i32]
+    lib.duo_set_decode_kernel.argtypes = [vp, i32]
     lib.duo_kv_append.argtypes = [vp, i32, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp]
     lib.duo_attn_prefill.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
     lib.duo_attn_decode.argtypes = [vp, i32, vp, vp, vp, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
@@ -164,6 +165,10 @@ def duo_cache_bytes(cache) -> int:
 
 def duo_set_decode_splits(cache, splits):
     _check(load().duo_set_decode_splits(cache, splits))
+
+
+def duo_set_decode_kernel(cache, kernel):
+    _check(load().duo_set_decode_kernel(cache, kernel))
 
 
 def duo_kv_append(cache, layer, k, v, n_new, params=None, stream=None):

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libduoattn.so")
 SYNTH_LIB = os.path.join(HERE, "libduosynth.so")
 
-SOURCES = ["duo_api.hip", "kernels_append.hip", "kernels_decode.hip", "kernels_prefill.hip"]
+SOURCES = ["duo_api.hip", "kernels_append.hip", "kernels_decode.hip", "kernels_decode_sk.hip", "kernels_prefill.hip"]
 SYNTH_SOURCES = ["synth_fill.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,5 +1,6 @@
 // Host side of libduoattn: handle management, argument validation, launches.
 // The C ABI is documented in include/duoattn.h.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -42,6 +43,7 @@ struct duo_cache {
   int32_t* tickets = nullptr;
   int max_splits = 0;
   int user_splits = 0;
+  bool force_matrix_decode = false;
   int64_t cache_bytes = 0;
 };
 
@@ -104,6 +106,31 @@ int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
   return (int)s;
 }
 
+// Workgroups that share the retrieval rows in the even-split decode kernel: one resident
+// workgroup per compute unit together with the streaming workgroups, a whole number per
+// segment while segments are few (no workgroup then crosses a segment border), and at least
+// kMinUnits units of 32 rows each.
+int choose_ret_workers(const duo_cache* c, const Layer& L, int64_t units_ret) {
+  const int64_t segs = (int64_t)L.view.n_ret * c->cfg.batch;
+  if (segs == 0) return 0;
+  const int64_t total = segs * units_ret;
+  const int64_t kMinUnits = 8;
+  int64_t w;
+  if (c->user_splits > 0) {
+    w = segs * c->user_splits;
+  } else {
+    int64_t budget = 256 - (int64_t)L.view.n_str * c->cfg.batch;
+    if (budget < 128) budget = 128;
+    w = segs <= budget ? segs * (budget / segs) : budget;
+    const int64_t by_len = total / kMinUnits;
+    if (w > by_len) w = segs <= by_len ? segs * (by_len / segs) : by_len;
+  }
+  if (w > duo::kMaxDecodeWorkers) w = duo::kMaxDecodeWorkers;
+  if (w > total) w = total;
+  if (w < 1) w = 1;
+  return (int)w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -134,8 +161,6 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
     return fail(DUO_EINVAL, "max_seq %lld exceeds the supported 2^31 - 1024", (long long)cfg->max_seq);
   if (cfg->kv_dtype != DUO_KV_BF16 && cfg->kv_dtype != DUO_KV_FP8_E4M3)
     return fail(DUO_EINVAL, "kv_dtype %d unknown", cfg->kv_dtype);
-  if (cfg->kv_dtype == DUO_KV_FP8_E4M3 && group == 8)
-    return fail(DUO_EINVAL, "query group size 8 is not supported with an fp8 cache");
   if (!cfg->retrieval_mask) return fail(DUO_EINVAL, "retrieval_mask must not be NULL");
   if (!(cfg->softmax_scale >= 0.0f) || std::isinf(cfg->softmax_scale))
     return fail(DUO_EINVAL, "softmax_scale must be finite and >= 0");
@@ -210,8 +235,13 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   if (e != hipSuccess) { release(c); return fail_hip(e, "hipMemcpy(tables)"); }
 
   c->max_splits = kMaxSplits;
-  e = dev_alloc(c, (void**)&c->part_o, (size_t)cfg->batch * hq * c->max_splits * cfg->head_dim * sizeof(float));
-  if (e == hipSuccess) e = dev_alloc(c, (void**)&c->part_ml, (size_t)cfg->batch * hq * c->max_splits * 2 * sizeof(float));
+  // split-K scratch: the larger of [batch][q head][split] rows and, for the even-split kernel,
+  // (workgroups + segments) rows per query head of a group
+  size_t part_rows = (size_t)cfg->batch * hq * c->max_splits;
+  const size_t sk_rows = ((size_t)duo::kMaxDecodeWorkers + (size_t)cfg->batch * hkv) * group;
+  if (sk_rows > part_rows) part_rows = sk_rows;
+  e = dev_alloc(c, (void**)&c->part_o, part_rows * cfg->head_dim * sizeof(float));
+  if (e == hipSuccess) e = dev_alloc(c, (void**)&c->part_ml, part_rows * 2 * sizeof(float));
   if (e == hipSuccess) e = dev_alloc(c, (void**)&c->tickets, (size_t)cfg->batch * hkv * sizeof(int32_t));
   if (e != hipSuccess) { release(c); return fail(DUO_ENOMEM, "hipMalloc(split-K scratch): %s", hipGetErrorString(e)); }
   e = hipMemset(c->tickets, 0, (size_t)cfg->batch * hkv * sizeof(int32_t));
@@ -249,6 +279,13 @@ int duo_set_decode_splits(duo_cache_t* c, int splits) {
   if (splits < 0 || splits > c->max_splits)
     return fail(DUO_ERANGE, "splits %d outside [0, %d]", splits, c->max_splits);
   c->user_splits = splits;
+  return DUO_OK;
+}
+
+int duo_set_decode_kernel(duo_cache_t* c, int kernel) {
+  if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
+  if (kernel != 0 && kernel != 1) return fail(DUO_EINVAL, "kernel must be 0 (automatic) or 1 (matrix-core), got %d", kernel);
+  c->force_matrix_decode = kernel == 1;
   return DUO_OK;
 }
 
@@ -306,7 +343,20 @@ static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k
   a.part_o = c->part_o; a.part_ml = c->part_ml; a.tickets = c->tickets; a.cache_len = L.len;
   a.splits = choose_splits(c, L, L.len);
   a.commit = commit ? 1 : 0;
-  hipError_t e = duo::launch_decode(a, (hipStream_t)stream);
+  hipError_t e;
+  // one query head per KV head on a bf16 cache: the vector-unit kernel; query groups and fp8
+  // caches: the matrix-core kernel
+  const bool use_sk = c->force_matrix_decode || L.view.group >= 2 || c->cfg.kv_dtype == DUO_KV_FP8_E4M3;
+  if (use_sk) {
+    const int64_t unit = duo::kDecodeUnitRows;
+    const int64_t rows_str = duo::streaming_rows(L.len, c->cfg.sink, c->cfg.recent);
+    a.units_ret = (int32_t)std::max<int64_t>(1, (L.len + unit - 1) / unit);
+    a.units_str = (int32_t)std::max<int64_t>(1, (rows_str + unit - 1) / unit);
+    a.ret_workers = choose_ret_workers(c, L, a.units_ret);
+    e = duo::launch_decode_sk(a, (hipStream_t)stream);
+  } else {
+    e = duo::launch_decode(a, (hipStream_t)stream);
+  }
   if (e != hipSuccess) return fail_hip(e, "decode launch");
   if (commit) L.len += 1;
   return DUO_OK;

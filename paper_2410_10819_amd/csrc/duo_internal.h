@@ -15,6 +15,9 @@ constexpr uint32_t kRetrievalBit = 0x80000000u;
 
 // Upper bound on key splits per retrieval head in decode (sizes the scratch).
 constexpr int kMaxDecodeSplits = 256;
+// Even-split decode: rows per work unit and the largest grid (sizes the scratch).
+constexpr int kDecodeUnitRows = 32;
+constexpr int kMaxDecodeWorkers = 1024;
 
 // Device view of one layer's two caches.  Layouts (row = one token of one head):
 //   retrieval: [batch][n_ret][max_seq][row_bytes]            (+ scales [batch][n_ret][max_seq])
@@ -56,6 +59,10 @@ struct DecodeArgs {
   int64_t cache_len;   // tokens held by the cache
   int32_t splits;      // key splits per retrieval head
   int32_t commit;      // write k_new / v_new into the caches (position cache_len)
+  // even-split kernel: units of kDecodeUnitRows rows per retrieval / streaming segment (>= 1 each);
+  // partial rows are indexed workgroup + segment, tickets by segment
+  int32_t units_ret, units_str;
+  int32_t ret_workers;  // workgroups sharing the retrieval units (0 if the layer has no retrieval head)
 };
 
 struct PrefillArgs {
@@ -75,6 +82,7 @@ hipError_t launch_export(const LayerView& lv, int batch_idx, int kv_head, int64_
                          void* k_out, void* v_out, float* ks_out, float* vs_out,
                          int64_t* pos_out, int64_t count, hipStream_t stream);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_decode_sk(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
 
 // Number of rows a streaming cache holds after `len` appends.

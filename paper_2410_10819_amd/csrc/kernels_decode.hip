@@ -519,29 +519,18 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   }
 }
 
-template <int D, bool FP8>
-hipError_t launch_dg(const DecodeArgs& a, dim3 grid, hipStream_t stream) {
-  switch (a.lv.group) {
-    case 1: decode_kernel<D, 1, FP8><<<grid, 256, 0, stream>>>(a); break;
-    case 2: decode_kernel<D, 2, FP8><<<grid, 256, 0, stream>>>(a); break;
-    case 4: decode_kernel<D, 4, FP8><<<grid, 256, 0, stream>>>(a); break;
-    case 8:
-      if constexpr (FP8) return hipErrorInvalidValue;
-      else decode_kernel<D, 8, false><<<grid, 256, 0, stream>>>(a);
-      break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
-}
-
 }  // namespace
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
   const LayerView& lv = a.lv;
+  // this kernel serves one query head per KV head on a bf16 cache; everything else goes to the
+  // matrix-core kernel
+  if (lv.group != 1 || lv.fp8) return hipErrorInvalidValue;
   if (a.splits < 1 || a.splits > kMaxDecodeSplits) return hipErrorInvalidValue;
   dim3 grid(lv.n_ret * a.splits + lv.n_str, lv.batch);
-  if (lv.head_dim == 128) return lv.fp8 ? launch_dg<128, true>(a, grid, stream) : launch_dg<128, false>(a, grid, stream);
-  return lv.fp8 ? launch_dg<64, true>(a, grid, stream) : launch_dg<64, false>(a, grid, stream);
+  if (lv.head_dim == 128) decode_kernel<128, 1, false><<<grid, 256, 0, stream>>>(a);
+  else decode_kernel<64, 1, false><<<grid, 256, 0, stream>>>(a);
+  return hipGetLastError();
 }
 
 }  // namespace duo

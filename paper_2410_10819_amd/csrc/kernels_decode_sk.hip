@@ -1,0 +1,641 @@
+// Decode attention on the matrix cores, with an even split of all cache rows
+// over the workgroups (paper, Section 2.3, Decoding; attention definitions of
+// Section 2.2).
+//
+// One decoding step reads every cached K and V row of the retrieval heads and at
+// most sink + recent rows of the streaming heads once: HBM-bound.  The design
+// keeps the arithmetic per byte small and the number of bytes in flight large:
+//   - Work split.  The rows of all retrieval (sequence, KV head) "segments" are cut
+//     into units of 32 rows and the units are dealt out evenly and contiguously
+//     to W workgroups, whatever the head count, batch and context length.  A
+//     workgroup whose range crosses a segment border handles both pieces; a
+//     segment handled by several workgroups is merged by the last of them to
+//     finish (ticket per segment, fixed merge order: deterministic).  Every
+//     streaming segment (at most sink + recent rows) has a workgroup of its own.
+//   - Arithmetic.  The G query heads of a KV head form the (padded) 16-wide side
+//     of 16x16x32 bf16 matrix-core products: S^T = K Q^T for 16 keys at a time,
+//     O^T += V^T P^T for 32 keys at a time.  A lane owns one head column, so the
+//     scores come out exactly where the probabilities are needed as the second
+//     product's operand, and a lane's accumulators all belong to one head.
+//     The running maximum is only re-synchronised across lanes when some score
+//     exceeds it (rare after the first blocks).
+//   - Data movement.  K goes from global memory straight into the matrix-core
+//     operand registers; V is staged through a wavefront-private LDS buffer
+//     (swizzled rows) and read back transposed.  Each wavefront works on its own
+//     32-row blocks with the loads of the next three blocks in flight (one
+//     workgroup per compute unit, registers instead of occupancy); no workgroup
+//     barrier in the main loop.
+//   - fp8 caches: codes are widened to bf16 on the way (exact), the K scale
+//     multiplies the score and the V scale the probability of its key.
+#include "duo_internal.h"
+
+namespace duo {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kUnit = kDecodeUnitRows;   // rows per unit = rows per wavefront block
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ inline int uniform_load(const int32_t* p) {
+  return *(const __attribute__((address_space(4))) int32_t*)(uintptr_t)p;
+}
+__device__ inline void coherent_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448.
+__device__ inline uint32_t e4m3_encode(float x) {
+  uint32_t u = __float_as_uint(x);
+  uint32_t sign = (u >> 24) & 0x80u;
+  u &= 0x7FFFFFFFu;
+  float a = __uint_as_float(u);
+  uint32_t code;
+  if (a >= 448.0f) {
+    code = 0x7Eu;
+  } else if (a < 0.015625f) {
+    code = (uint32_t)rintf(a * 512.0f);
+  } else {
+    uint32_t r = u + 0x7FFFFu + ((u >> 20) & 1u);
+    code = (r >> 20) - ((127u - 7u) << 3);
+  }
+  return code | sign;
+}
+
+// Four E4M3 codes (one dword) -> four bf16 values (two dwords); exact.
+__device__ inline uint2 e4m3x4_to_bf16x4(uint32_t w) {
+  const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+  const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  // every E4M3 value has at most 4 significant bits, so the upper halves of the floats are the
+  // bf16 values: one byte permute packs two of them
+  uint2 r;
+  r.x = __builtin_amdgcn_perm(__float_as_uint(lo[1]), __float_as_uint(lo[0]), 0x07060302u);
+  r.y = __builtin_amdgcn_perm(__float_as_uint(hi[1]), __float_as_uint(hi[0]), 0x07060302u);
+  return r;
+}
+
+template <int D, bool FP8>
+struct Shape {
+  static constexpr int NKK = D / 32;                 // matrix-core k-steps of K Q^T
+  static constexpr int NMB = D / 16;                 // 16-row blocks of O^T
+  static constexpr int LROW = D * 2;                 // bytes of a (bf16) V row in LDS
+  static constexpr int CPR = D / 8;                  // 16-byte pieces per LDS row
+  static constexpr int GROW = FP8 ? D : D * 2;       // bytes of a row in the cache
+  static constexpr int VPR = GROW / 16;              // 16-byte pieces per cache row
+  static constexpr int VRPI = 64 / VPR;              // V rows covered by one wavefront load
+  static constexpr int NV = kUnit / VRPI;            // V loads per lane and block
+  static constexpr int KB = FP8 ? 8 : 16;            // bytes of K per lane, 16-key group and k-step
+  __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
+};
+
+// Raw registers of one 32-row block as loaded from the cache.
+template <int D, bool FP8>
+struct RawBlock {
+  using S = Shape<D, FP8>;
+  uint32_t k[2][S::NKK][S::KB / 4];
+  uint4 v[S::NV];
+  float sc;   // fp8: K scale of row `lane` (lanes 0..31) or V scale of row `lane - 32`
+};
+
+template <int D, bool FP8>
+__global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
+  using S = Shape<D, FP8>;
+  constexpr int NKK = S::NKK, NMB = S::NMB, LROW = S::LROW, GROW = S::GROW;
+  const LayerView& lv = a.lv;
+  const int G = lv.group;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: block addresses stay uniform
+  const int hd = lane & 15, qd = lane >> 4;
+  const bool head_ok = hd < G;
+
+  // LDS: per-wavefront V staging; later reused for the merges.
+  __shared__ __attribute__((aligned(16))) uint8_t sm_v[4][kUnit * LROW];
+  __shared__ __attribute__((aligned(16))) float sm_sc[4][64];
+  __shared__ __attribute__((aligned(16))) uint16_t sm_new[2][D];
+  __shared__ float sm_m[4][16], sm_l[4][16], sm_m2[16], sm_l2[16];
+  __shared__ int sm_last;
+  float* sm_o = (float*)&sm_v[0][0];   // [wave][head][D] or [slot][D]: 4 * 16 * D floats at most
+  uint8_t* my_v = &sm_v[wave][0];
+
+  // Workgroups 0 .. W-1 share the units of the retrieval segments evenly; each streaming segment
+  // (at most sink + recent rows) has a workgroup of its own after them.
+  const int64_t n_ret_seg = (int64_t)lv.batch * lv.n_ret;
+  const int64_t ret_units_all = n_ret_seg * a.units_ret;
+  const int64_t T = ret_units_all, W = a.ret_workers;
+  int64_t u_lo, u_hi;
+  if ((int64_t)blockIdx.x < W) {
+    u_lo = (int64_t)blockIdx.x * T / W;
+    u_hi = ((int64_t)blockIdx.x + 1) * T / W;
+  } else {
+    u_lo = ret_units_all + ((int64_t)blockIdx.x - W) * a.units_str;
+    u_hi = u_lo + a.units_str;
+  }
+  const float c_scale = lv.scale * kLog2e;
+
+  for (int64_t u = u_lo; u < u_hi;) {
+    // ---- the segment that owns unit u
+    int64_t seg, seg_a;
+    int seg_units, b, slot, kvh;
+    int64_t n_rows, exclude = -1, new_row;
+    uint8_t *kbase, *vbase;
+    float *ksbase = nullptr, *vsbase = nullptr;
+    const bool retrieval = u < ret_units_all;
+    if (retrieval) {
+      seg = u / a.units_ret;
+      seg_a = seg * a.units_ret;
+      seg_units = a.units_ret;
+      b = (int)(seg / lv.n_ret); slot = (int)(seg % lv.n_ret);
+      kvh = uniform_load(lv.ret_heads + slot);
+      n_rows = a.cache_len;
+      new_row = a.cache_len;
+      const int64_t head_row0 = ((int64_t)b * lv.n_ret + slot) * lv.max_seq;
+      kbase = lv.k_ret + head_row0 * GROW;
+      vbase = lv.v_ret + head_row0 * GROW;
+      if (FP8) { ksbase = lv.ks_ret + head_row0; vsbase = lv.vs_ret + head_row0; }
+    } else {
+      const int64_t s2 = (u - ret_units_all) / a.units_str;
+      seg = n_ret_seg + s2;
+      seg_a = ret_units_all + s2 * a.units_str;
+      seg_units = a.units_str;
+      b = (int)(s2 / lv.n_str); slot = (int)(s2 % lv.n_str);
+      kvh = uniform_load(lv.str_heads + slot);
+      const int64_t cap = (int64_t)lv.sink + lv.recent;
+      n_rows = streaming_rows(a.cache_len, lv.sink, lv.recent);
+      // The slot the new token goes to: while it is not yet written, that slot of a
+      // full ring still holds the token the append evicts, which the query at
+      // position cache_len must not see.
+      new_row = a.cache_len < lv.sink ? a.cache_len : lv.sink + (a.cache_len - lv.sink) % lv.recent;
+      if (a.k_new != nullptr && a.cache_len >= cap) exclude = new_row;
+      const int64_t head_row0 = ((int64_t)b * lv.n_str + slot) * cap;
+      kbase = lv.k_str + head_row0 * GROW;
+      vbase = lv.v_str + head_row0 * GROW;
+      if (FP8) { ksbase = lv.ks_str + head_row0; vsbase = lv.vs_str + head_row0; }
+    }
+    const int64_t seg_e = seg_a + seg_units;
+    const int64_t part_e = u_hi < seg_e ? u_hi : seg_e;
+    const int64_t row0 = (u - seg_a) * kUnit;                      // first row of this workgroup's part
+    int64_t row1 = (part_e - seg_a) * kUnit;                       // end of the part, clipped to the rows present
+    if (row1 > n_rows) row1 = n_rows;
+    const int nb = row1 > row0 ? (int)((row1 - row0 + kUnit - 1) / kUnit) : 0;
+    const bool with_new = a.k_new != nullptr && part_e == seg_e;   // the part that ends the segment owns the new token
+    const int64_t last_row = n_rows > 0 ? n_rows - 1 : 0;
+
+    // ---- query operand: lane (hd, qd) holds q[head hd][32 kk + 8 qd .. + 7]
+    bf16x8 qf[NKK];
+    {
+      const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G + (head_ok ? hd : 0)) * D;
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        uint4 raw = *(const uint4*)(qrow + 32 * kk + 8 * qd);
+        if (!head_ok) raw = make_uint4(0, 0, 0, 0);
+        qf[kk] = __builtin_bit_cast(bf16x8, raw);
+      }
+    }
+
+    // ---- per-wavefront online-softmax state
+    f32x4 oacc[NMB];
+#pragma unroll
+    for (int mb = 0; mb < NMB; ++mb) oacc[mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_ref = -INFINITY, l_lane = 0.f;
+
+    using Raw = RawBlock<D, FP8>;
+    // Loads of a block whose 32 rows are all present: a uniform block address plus per-lane
+    // offsets that never change (K: row hd of each 16-key group, piece qd + 4 kk; V: the block's
+    // rows are one contiguous run, 16 bytes per lane and load).
+    const uint32_t k_off = (uint32_t)(hd * GROW + qd * S::KB);
+    const uint32_t v_off = (uint32_t)(lane * 16);
+    auto issue = [&](Raw& rb, int blk) {
+      const int64_t r0 = row0 + (int64_t)blk * kUnit;
+      const uint8_t* kb = kbase + r0 * GROW;
+      const uint8_t* vb = vbase + r0 * GROW;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          const uint8_t* p = kb + (k_off + (uint32_t)(16 * t * GROW + 4 * kk * S::KB));
+          if constexpr (FP8) {
+            const uint2 x = *(const uint2*)p;
+            rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y;
+          } else {
+            const uint4 x = *(const uint4*)p;
+            rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y; rb.k[t][kk][2] = x.z; rb.k[t][kk][3] = x.w;
+          }
+        }
+#pragma unroll
+      for (int j = 0; j < S::NV; ++j) rb.v[j] = *(const uint4*)(vb + (v_off + (uint32_t)(j * 1024)));
+      if constexpr (FP8) rb.sc = (lane < 32 ? ksbase : vsbase)[r0 + (lane & 31)];
+    };
+    // The same for the last, partly filled block of a segment: rows past the end are redirected
+    // to the last row present (and masked later).
+    auto issue_tail = [&](Raw& rb, int blk) {
+      const int64_t r0 = row0 + (int64_t)blk * kUnit;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        int64_t r = r0 + 16 * t + hd;
+        r = r < n_rows ? r : last_row;
+        const uint8_t* kr = kbase + r * GROW;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          if constexpr (FP8) {
+            const uint2 x = *(const uint2*)(kr + (qd + 4 * kk) * 8);
+            rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y;
+          } else {
+            const uint4 x = *(const uint4*)(kr + (qd + 4 * kk) * 16);
+            rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y; rb.k[t][kk][2] = x.z; rb.k[t][kk][3] = x.w;
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < S::NV; ++j) {
+        int64_t r = r0 + j * S::VRPI + lane / S::VPR;
+        r = r < n_rows ? r : last_row;
+        rb.v[j] = *(const uint4*)(vbase + r * GROW + (lane % S::VPR) * 16);
+      }
+      if constexpr (FP8) {
+        int64_t r = r0 + (lane & 31);
+        r = r < n_rows ? r : last_row;
+        rb.sc = (lane < 32 ? ksbase : vsbase)[r];
+      }
+    };
+
+    // S^T = K Q^T for the two 16-key groups of a block.
+    auto qk = [&](const bf16x8 (&kf)[2][NKK], f32x4 (&sacc)[2]) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        sacc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+          sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][kk], qf[kk], sacc[t], 0, 0, 0);
+      }
+    };
+    // Softmax update and O^T += V^T P^T of one block whose V rows are staged in my_v (bf16).
+    // key_base: row index of the block's first key; keys >= valid_end are masked.
+    auto finish = [&](const f32x4 (&sacc)[2], const float (&ksc)[8], const float (&vsc)[8],
+                      int64_t key_base, int64_t valid_end) {
+      float sv[8];
+      float lmax = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t key = key_base + 16 * t + 4 * qd + r;
+          float s = sacc[t][r] * c_scale;
+          if constexpr (FP8) s *= ksc[4 * t + r];
+          const bool ok = head_ok && key < valid_end && key != exclude;
+          s = ok ? s : -INFINITY;
+          sv[4 * t + r] = s;
+          lmax = fmaxf(lmax, s);
+        }
+      if (__ballot(lmax > m_ref) != 0) {
+        float mx = fmaxf(lmax, __shfl_xor(lmax, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_ref, mx);
+        const float mu = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = fast_exp2(m_ref - mu);
+        l_lane *= alpha;
+#pragma unroll
+        for (int mb = 0; mb < NMB; ++mb) oacc[mb] *= alpha;
+        m_ref = m_new;
+      }
+      const float mu = m_ref == -INFINITY ? 0.f : m_ref;
+      float p[8];
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { p[i] = fast_exp2(sv[i] - mu); psum += p[i]; }
+      l_lane += psum;
+      bf16x8 pb;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pb[i] = (__bf16)(FP8 ? p[i] * vsc[i] : p[i]);
+      // O^T += V^T P^T : lane (hd, qd) supplies the address of key 16 h + 4 qd + (hd >> 2), d 16 mb + 4 (hd & 3)
+      const int e = hd >> 2, i4 = hd & 3;
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb) {
+        const int piece = 2 * mb + (i4 >> 1), sub8 = (i4 & 1) * 8;
+        const int key_lo = 4 * qd + e, key_hi = 16 + 4 * qd + e;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            LDS_PTR(s16x4, my_v + key_lo * LROW + ((piece ^ S::v_swz(key_lo)) * 16) + sub8));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            LDS_PTR(s16x4, my_v + key_hi * LROW + ((piece ^ S::v_swz(key_hi)) * 16) + sub8));
+        const bf16x8 vt = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        oacc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb, oacc[mb], 0, 0, 0);
+      }
+    };
+
+    // Convert / stage the raw registers of a block (V rows into the wavefront's LDS buffer, 16-byte
+    // pieces swizzled by row; fp8 scales through LDS into key order) and start its arithmetic.
+    // After this the raw registers are free for the next block's loads.
+    auto stage_qk = [&](const Raw& rb, f32x4 (&sacc)[2], float (&ksc)[8], float (&vsc)[8]) {
+#pragma unroll
+      for (int j = 0; j < S::NV; ++j) {
+        const int row = j * S::VRPI + lane / S::VPR, pc = lane % S::VPR;
+        if constexpr (FP8) {
+          const uint2 a0 = e4m3x4_to_bf16x4(rb.v[j].x), a1 = e4m3x4_to_bf16x4(rb.v[j].y);
+          const uint2 a2 = e4m3x4_to_bf16x4(rb.v[j].z), a3 = e4m3x4_to_bf16x4(rb.v[j].w);
+          *(uint4*)(my_v + row * LROW + (((2 * pc) ^ S::v_swz(row)) * 16)) = make_uint4(a0.x, a0.y, a1.x, a1.y);
+          *(uint4*)(my_v + row * LROW + (((2 * pc + 1) ^ S::v_swz(row)) * 16)) = make_uint4(a2.x, a2.y, a3.x, a3.y);
+        } else {
+          *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = rb.v[j];
+        }
+      }
+      bf16x8 kf[2][NKK];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          if constexpr (FP8) {
+            const uint2 x0 = e4m3x4_to_bf16x4(rb.k[t][kk][0]), x1 = e4m3x4_to_bf16x4(rb.k[t][kk][1]);
+            kf[t][kk] = __builtin_bit_cast(bf16x8, make_uint4(x0.x, x0.y, x1.x, x1.y));
+          } else {
+            kf[t][kk] = __builtin_bit_cast(bf16x8, make_uint4(rb.k[t][kk][0], rb.k[t][kk][1], rb.k[t][kk][2], rb.k[t][kk][3]));
+          }
+        }
+      qk(kf, sacc);
+      if constexpr (FP8) {
+        sm_sc[wave][lane] = rb.sc;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const float4 kq = *(const float4*)&sm_sc[wave][16 * t + 4 * qd];
+          const float4 vq = *(const float4*)&sm_sc[wave][32 + 16 * t + 4 * qd];
+          ksc[4 * t] = kq.x; ksc[4 * t + 1] = kq.y; ksc[4 * t + 2] = kq.z; ksc[4 * t + 3] = kq.w;
+          vsc[4 * t] = vq.x; vsc[4 * t + 1] = vq.y; vsc[4 * t + 2] = vq.z; vsc[4 * t + 3] = vq.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { ksc[i] = 1.f; vsc[i] = 1.f; }
+      }
+    };
+
+    // ---- main loop: this wavefront's full blocks wave, wave + 4, ...  Three sets of raw
+    // registers rotate: as soon as a block is staged and its K products are issued, its registers
+    // take the loads of the block three turns ahead, so up to three blocks (48 KiB of bf16 K/V)
+    // are in flight per wavefront.  In the steady loop every issue is unconditional, which lets
+    // the compiler's wait counts match the real queue; the scheduling barriers keep the loads
+    // where they are written.  Then the partly filled last block, if any, by the wavefront whose
+    // turn it is.
+    const int n_full = (int)((row1 - row0) / kUnit) < nb ? (int)((row1 - row0) / kUnit) : nb;
+    {
+      Raw r0, r1, r2;
+      f32x4 sacc[2];
+      float ksc[8], vsc[8];
+      const int n_my = wave < n_full ? (n_full - wave + 3) / 4 : 0;   // blocks of this wavefront
+      auto blk_of = [&](int i) { return wave + 4 * i; };
+      auto step = [&](Raw& rb, int i, bool prefetch) {
+        stage_qk(rb, sacc, ksc, vsc);
+        __builtin_amdgcn_sched_barrier(0);
+        if (prefetch) issue(rb, blk_of(i + 3));
+        __builtin_amdgcn_sched_barrier(0);
+        finish(sacc, ksc, vsc, row0 + (int64_t)blk_of(i) * kUnit, n_rows);
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      if (n_my > 0) issue(r0, blk_of(0));
+      if (n_my > 1) issue(r1, blk_of(1));
+      if (n_my > 2) issue(r2, blk_of(2));
+      __builtin_amdgcn_sched_barrier(0);
+      int i = 0;
+      while (i + 5 < n_my) {
+        step(r0, i, true);
+        step(r1, i + 1, true);
+        step(r2, i + 2, true);
+        i += 3;
+      }
+      while (i < n_my) {
+        step(r0, i, i + 3 < n_my);
+        if (i + 1 < n_my) step(r1, i + 1, i + 4 < n_my);
+        if (i + 2 < n_my) step(r2, i + 2, i + 5 < n_my);
+        i += 3;
+      }
+      if (n_full < nb && wave == (n_full & 3)) {
+        issue_tail(r0, n_full);
+        stage_qk(r0, sacc, ksc, vsc);
+        finish(sacc, ksc, vsc, row0 + (int64_t)n_full * kUnit, n_rows);
+      }
+    }
+
+    // ---- the new token (wavefront 0 of the part that ends the segment); with a.commit its rows
+    // are also written into the cache
+    if (with_new && wave == 0) {
+      // row layout: lane i < D/8 owns elements 8 i .. 8 i + 7
+      const bool row_lane = lane < D / 8;
+      const uint16_t* kin = (const uint16_t*)a.k_new + ((int64_t)b * lv.n_kv_heads + kvh) * D;
+      const uint16_t* vin = (const uint16_t*)a.v_new + ((int64_t)b * lv.n_kv_heads + kvh) * D;
+      uint4 kc = make_uint4(0, 0, 0, 0), vc = kc;
+      if (row_lane) { kc = *(const uint4*)(kin + 8 * lane); vc = *(const uint4*)(vin + 8 * lane); }
+      float ks1 = 1.f, vs1 = 1.f;
+      if constexpr (!FP8) {
+        if (a.commit && row_lane) {
+          *(uint4*)(kbase + new_row * GROW + lane * 16) = kc;
+          *(uint4*)(vbase + new_row * GROW + lane * 16) = vc;
+        }
+      } else {
+        // quantise exactly as the append kernel does, then attend to the dequantised row
+        const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w}, vw[4] = {vc.x, vc.y, vc.z, vc.w};
+        float kf8[8], vf8[8], kmax = 0.f, vmax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          kf8[2 * i] = __uint_as_float(kw[i] << 16); kf8[2 * i + 1] = __uint_as_float(kw[i] & 0xFFFF0000u);
+          vf8[2 * i] = __uint_as_float(vw[i] << 16); vf8[2 * i + 1] = __uint_as_float(vw[i] & 0xFFFF0000u);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { kmax = fmaxf(kmax, fabsf(kf8[i])); vmax = fmaxf(vmax, fabsf(vf8[i])); }
+#pragma unroll
+        for (int off = 1; off < D / 8; off <<= 1) {
+          kmax = fmaxf(kmax, __shfl_xor(kmax, off));
+          vmax = fmaxf(vmax, __shfl_xor(vmax, off));
+        }
+        ks1 = kmax == 0.f ? 1.0f : kmax / 448.0f;
+        vs1 = vmax == 0.f ? 1.0f : vmax / 448.0f;
+        uint32_t kq[2] = {0, 0}, vq[2] = {0, 0};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          kq[i / 4] |= e4m3_encode(kf8[i] / ks1) << (8 * (i % 4));
+          vq[i / 4] |= e4m3_encode(vf8[i] / vs1) << (8 * (i % 4));
+        }
+        if (a.commit && row_lane) {
+          *(uint2*)(kbase + new_row * GROW + lane * 8) = make_uint2(kq[0], kq[1]);
+          *(uint2*)(vbase + new_row * GROW + lane * 8) = make_uint2(vq[0], vq[1]);
+          if (lane == 0) { ksbase[new_row] = ks1; vsbase[new_row] = vs1; }
+        }
+        const uint2 k0 = e4m3x4_to_bf16x4(kq[0]), k1 = e4m3x4_to_bf16x4(kq[1]);
+        const uint2 v0 = e4m3x4_to_bf16x4(vq[0]), v1 = e4m3x4_to_bf16x4(vq[1]);
+        kc = make_uint4(k0.x, k0.y, k1.x, k1.y);
+        vc = make_uint4(v0.x, v0.y, v1.x, v1.y);
+        ks1 = __shfl(ks1, 0); vs1 = __shfl(vs1, 0);
+      }
+      // the (dequantised) bf16 rows through LDS into the operand layouts: K as key 0 of a block
+      // whose other keys are masked, V as every row of the staging buffer
+      if (row_lane) { *(uint4*)&sm_new[0][8 * lane] = kc; *(uint4*)&sm_new[1][8 * lane] = vc; }
+      bf16x8 kf[2][NKK];
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        uint4 x = *(const uint4*)&sm_new[0][32 * kk + 8 * qd];
+        if (hd != 0) x = make_uint4(0, 0, 0, 0);
+        kf[0][kk] = __builtin_bit_cast(bf16x8, x);
+        kf[1][kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+      }
+#pragma unroll
+      for (int j = 0; j < kUnit * S::CPR / 64; ++j) {
+        const int row = j * (64 / S::CPR) + lane / S::CPR, pc = lane % S::CPR;
+        *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
+      }
+      float ksc[8], vsc[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { ksc[i] = ks1; vsc[i] = vs1; }
+      const int64_t saved = exclude;
+      exclude = -1;
+      f32x4 sacc[2];
+      qk(kf, sacc);
+      finish(sacc, ksc, vsc, 0, 1);   // keys 0 .. 31 of a virtual block, only key 0 valid
+      exclude = saved;
+    }
+
+    // ---- merge the four wavefronts through LDS
+    float l_head = l_lane + __shfl_xor(l_lane, 16);
+    l_head += __shfl_xor(l_head, 32);
+    __syncthreads();   // every wavefront is done with its V staging buffer
+    if (head_ok) {
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm_o[(wave * 16 + hd) * D + 16 * mb + 4 * qd + r] = oacc[mb][r];
+      if (qd == 0) { sm_m[wave][hd] = m_ref; sm_l[wave][hd] = l_head; }
+    }
+    __syncthreads();
+    // retrieval workgroups that share this segment: those owning its first and last unit
+    const int64_t w_first = retrieval ? ((seg_a + 1) * W + T - 1) / T - 1 : 0;
+    const int64_t w_last = retrieval ? (seg_e * W + T - 1) / T - 1 : 0;
+    const int n_parts = (int)(w_last - w_first + 1);
+    const int64_t part_row = (int64_t)blockIdx.x + seg;   // unique per (workgroup, segment) pair
+    for (int idx = tid; idx < G * D; idx += 256) {
+      const int g = idx / D, d = idx % D;
+      float mn = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) mn = fmaxf(mn, sm_m[w][g]);
+      const float mu = mn == -INFINITY ? 0.f : mn;
+      float acc = 0.f, ls = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float wgt = fast_exp2(sm_m[w][g] - mu);
+        acc += wgt * sm_o[(w * 16 + g) * D + d];
+        ls += wgt * sm_l[w][g];
+      }
+      const int h = kvh * G + g;
+      if (n_parts == 1) {
+        ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + h) * D + d] = f32_to_bf16(acc / ls);
+        if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + h] = (mn + log2f(ls)) * kLn2;
+      } else {
+        const int64_t pi = part_row * G + g;
+        coherent_store(a.part_o + pi * D + d, acc);
+        if (d == 0) { coherent_store(a.part_ml + pi * 2, mn); coherent_store(a.part_ml + pi * 2 + 1, ls); }
+      }
+    }
+    if (n_parts > 1) {
+      // Ticket: the last workgroup of this segment to get here merges the partials.  They are
+      // written and read with device-scope accesses; waiting for the stores to be acknowledged
+      // before taking the ticket orders them without a cache write-back.
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      if (tid == 0) {
+        int* ticket = a.tickets + seg;
+        const int prev = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_last = prev == n_parts - 1;
+        if (sm_last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+      }
+      __syncthreads();
+      if (sm_last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        // All heads of the group at once: 256 threads = SLOTS rows of TPR threads (one float4 of a
+        // partial row each); head g owns NP consecutive slots; slot `part` of a head folds the
+        // partials part, part + NP, ... in that order, then the NP slot results are merged in
+        // slot order - a fixed order, so the result is deterministic.
+        constexpr int TPR = D / 4, SLOTS = 256 / TPR;
+        const int NP = SLOTS / G;                       // G in {1, 2, 4, 8} divides SLOTS
+        const int dq = tid % TPR, slot_id = tid / TPR;
+        const int mg = slot_id / NP, part = slot_id % NP;
+        {
+          const float2* ml = (const float2*)a.part_ml;
+          const float4* po = (const float4*)a.part_o;
+          const int64_t first = (w_first + seg) * G + mg;   // partial row of part 0, stride G rows per part
+          float mr = -INFINITY, lr = 0.f;
+          float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+          constexpr int B4 = 16;   // partial rows fetched together: one memory round trip per batch
+          for (int s0 = part; s0 < n_parts; s0 += NP * B4) {
+            float2 mlv[B4];
+            float4 x[B4];
+#pragma unroll
+            for (int j = 0; j < B4; ++j) {
+              const int sidx = s0 + j * NP;
+              const int sc = sidx < n_parts ? sidx : n_parts - 1;
+              const int64_t pr = first + (int64_t)sc * G;
+              mlv[j] = ml[pr];
+              x[j] = po[pr * TPR + dq];
+              if (sidx >= n_parts) mlv[j] = make_float2(-INFINITY, 0.f);
+            }
+#pragma unroll
+            for (int j = 0; j < B4; ++j) {
+              const float mn = fmaxf(mr, mlv[j].x);
+              const float mu = mn == -INFINITY ? 0.f : mn;
+              const float a1 = fast_exp2(mr - mu), a2 = fast_exp2(mlv[j].x - mu);
+              lr = lr * a1 + mlv[j].y * a2;
+              acc.x = acc.x * a1 + x[j].x * a2; acc.y = acc.y * a1 + x[j].y * a2;
+              acc.z = acc.z * a1 + x[j].z * a2; acc.w = acc.w * a1 + x[j].w * a2;
+              mr = mn;
+            }
+          }
+          __syncthreads();   // sm_o is free again
+          *(float4*)(sm_o + slot_id * D + 4 * dq) = acc;
+          if (dq == 0) { sm_m2[slot_id] = mr; sm_l2[slot_id] = lr; }
+        }
+        __syncthreads();
+        for (int idx = tid; idx < G * D; idx += 256) {
+          const int g = idx / D, d = idx % D;
+          float mn = -INFINITY;
+          for (int pp = 0; pp < NP; ++pp) mn = fmaxf(mn, sm_m2[g * NP + pp]);
+          float tot = 0.f, ls = 0.f;
+          for (int pp = 0; pp < NP; ++pp) {
+            const float wgt = fast_exp2(sm_m2[g * NP + pp] - mn);
+            tot += wgt * sm_o[(g * NP + pp) * D + d];
+            ls += wgt * sm_l2[g * NP + pp];
+          }
+          const int h = kvh * G + g;
+          ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + h) * D + d] = f32_to_bf16(tot / ls);
+          if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + h] = (mn + log2f(ls)) * kLn2;
+        }
+      }
+    }
+    u = part_e;
+    __syncthreads();   // LDS is reused by the next segment
+  }
+}
+
+}  // namespace
+
+hipError_t launch_decode_sk(const DecodeArgs& a, hipStream_t stream) {
+  const LayerView& lv = a.lv;
+  const int64_t ret_units = (int64_t)lv.batch * lv.n_ret * a.units_ret;
+  if (a.ret_workers < 0 || a.ret_workers > kMaxDecodeWorkers || (int64_t)a.ret_workers > ret_units ||
+      (ret_units > 0 && a.ret_workers < 1) || a.units_ret < 1 || a.units_str < 1)
+    return hipErrorInvalidValue;
+  dim3 grid((unsigned)(a.ret_workers + lv.batch * lv.n_str));
+  if (lv.head_dim == 128) {
+    if (lv.fp8) decode_sk_kernel<128, true><<<grid, 256, 0, stream>>>(a);
+    else decode_sk_kernel<128, false><<<grid, 256, 0, stream>>>(a);
+  } else {
+    if (lv.fp8) decode_sk_kernel<64, true><<<grid, 256, 0, stream>>>(a);
+    else decode_sk_kernel<64, false><<<grid, 256, 0, stream>>>(a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace duo

@@ -52,7 +52,6 @@ GOOD = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=8, head_dim=64, sink=16
     (dict(max_seq=2 ** 31), "max_seq"),
     (dict(kv_dtype=7), "kv_dtype"),
     (dict(softmax_scale=-1.0), "softmax_scale"),
-    (dict(n_q_heads=64, kv_dtype=1), "fp8"),
 ])
 def test_create_rejects_bad_configs_before_allocating(change, fragment):
     kw = dict(GOOD)

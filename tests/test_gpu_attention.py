@@ -233,3 +233,65 @@ def test_fp8_cache_decode(hq, hkv, d):
             assert np.abs(got_lse[b] - want_lse).max() <= ATOL_LSE
     finally:
         duo.duo_cache_destroy(handle)
+
+
+def _decode_vs_oracle(hq, hkv, d, sink, recent, batch, n_fill, n_decode, kv_dtype, mask, kernel=0, splits=0,
+                      check_batches=None, seed=91):
+    """Fill by append, then n_decode one-launch steps; every output row against the oracle."""
+    import torch
+    total = n_fill + n_decode
+    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=sink, recent=recent, mask=mask, max_seq=total,
+               kv_dtype=kv_dtype)
+    q, k, v = make_qkv(seed, batch, total, hq, hkv, d)
+    handle = duo.duo_cache_create(1, batch, hq, hkv, d, sink, recent, total, mask[None], kv_dtype)
+    try:
+        duo.duo_set_decode_kernel(handle, kernel)
+        duo.duo_set_decode_splits(handle, splits)
+        if n_fill:
+            duo.duo_kv_append(handle, 0, to_dev(k[:, :n_fill]), to_dev(v[:, :n_fill]), n_fill)
+        got = np.zeros((batch, n_decode, hq, d))
+        got_lse = np.zeros((batch, hq, n_decode))
+        for t in range(n_decode):
+            p = n_fill + t
+            qd, kd, vd = (to_dev(x[:, p:p + 1]) for x in (q, k, v))
+            od = torch.empty((batch, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+            ld = torch.empty((batch, hq), dtype=torch.float32, device="cuda")
+            duo.duo_decode_step(handle, 0, qd, kd, vd, od, lse=ld)
+            got[:, t] = from_dev_f64(od)[:, 0]
+            got_lse[:, :, t] = ld.cpu().numpy()
+        assert duo.duo_cache_len(handle, 0) == total
+    finally:
+        duo.duo_cache_destroy(handle)
+    for b in (range(batch) if check_batches is None else check_batches):
+        want_o, want_lse = oracle_rows(cfg, q, k, v, np.arange(n_fill, total), b)
+        assert_close(got[b], want_o, "batch %d" % b)
+        assert np.abs(got_lse[b] - want_lse).max() <= ATOL_LSE
+
+
+@pytest.mark.parametrize("d,kv_dtype", [(64, 0), (128, 0), (128, 1)])
+def test_matrix_core_decode_kernel_with_one_query_head_per_kv_head(d, kv_dtype):
+    # the matrix-core kernel forced onto an MHA layer (it pads the single head to 16 columns);
+    # the context starts empty-ish, crosses the 32-row unit size and wraps the ring
+    mask = np.array([1, 0, 1, 0], dtype=np.uint8)
+    _decode_vs_oracle(4, 4, d, 5, 40, 2, 27, 45, kv_dtype, mask, kernel=1)
+    _decode_vs_oracle(4, 4, d, 5, 40, 1, 0, 3, kv_dtype, mask, kernel=1)          # from an empty cache
+    _decode_vs_oracle(4, 4, d, 5, 40, 1, 1500, 4, kv_dtype, mask, kernel=1, splits=7)
+
+
+@pytest.mark.parametrize("kv_dtype", [0, 1])
+def test_query_group_of_eight(kv_dtype):
+    mask = np.array([0, 1], dtype=np.uint8)
+    _decode_vs_oracle(16, 2, 128, 4, 28, 2, 333, 6, kv_dtype, mask)
+    _decode_vs_oracle(16, 2, 64, 4, 28, 1, 95, 3, kv_dtype, mask, splits=3)
+
+
+def test_decode_workgroups_that_cross_segment_borders():
+    # more retrieval (sequence, head) segments than workgroups: every workgroup handles the end of
+    # one segment and the start of the next, and whole segments in between
+    mask = np.array([1, 0, 1, 1], dtype=np.uint8)
+    _decode_vs_oracle(8, 4, 64, 3, 20, 120, 210, 2, 0, mask, check_batches=(0, 57, 119))
+
+
+def test_all_streaming_and_all_retrieval_layers_on_the_matrix_core_kernel():
+    for mask in (np.zeros(2, dtype=np.uint8), np.ones(2, dtype=np.uint8)):
+        _decode_vs_oracle(8, 2, 128, 4, 16, 2, 150, 3, 0, mask)
