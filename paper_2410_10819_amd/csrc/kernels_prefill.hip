@@ -26,6 +26,8 @@
 // share the code: for a retrieval head it is positions 0 .. pos0+n-1 (cache
 // rows, then chunk rows); for a streaming head it is the retained sink slots,
 // the retained ring slots in position order, then the chunk rows.
+#include <type_traits>
+
 #include "duo_internal.h"
 
 namespace duo {
@@ -48,6 +50,38 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ inline float swap_halves(float x, int peer_byte_addr) {
   return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(peer_byte_addr, __builtin_bit_cast(int, x)));
 }
+#ifndef DUO_EXP_NW
+#define DUO_EXP_NW 8
+#endif
+// LDS reads of the matrix-core phase are written as inline assembly with hand-placed waits:
+// the compiler would tie them to the outstanding LDS-direct loads of later tiles (draining the
+// prefetch) and would not keep reads several products ahead of their use.  The wait helpers
+// name the registers they release so that no use can be scheduled above them.
+template <int OFF>
+__device__ inline s16x4 lds_read_tr16(uint32_t addr) {   // transposed 8-byte read, see pv_phase
+  s16x4 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+  return r;
+}
+template <int OFF>
+__device__ inline bf16x8 lds_read_b128(uint32_t addr) {
+  bf16x8 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+  return r;
+}
+template <int N>
+__device__ inline void lds_wait(s16x4& a, s16x4& b, s16x4& c, s16x4& d, s16x4& e, s16x4& f, s16x4& g, s16x4& h) {
+  asm volatile("s_waitcnt lgkmcnt(%8)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e), "+v"(f), "+v"(g), "+v"(h) : "n"(N) : "memory");
+}
+template <int N>
+__device__ inline void lds_wait(s16x4& a, s16x4& b, s16x4& c, s16x4& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+template <int N>
+__device__ inline void lds_wait(bf16x8& a, bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+__device__ inline uint32_t lds_addr(const uint8_t* p) { return (uint32_t)(uintptr_t)LDS_PTR(const uint8_t, p); }
 __device__ inline int clamp_i32(int64_t x) {
   const int64_t lim = 1 << 30;
   return (int)(x < -lim ? -lim : (x > lim ? lim : x));
@@ -85,6 +119,9 @@ struct KeySource {
 
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
+template <int N>
+using template_int = std::integral_constant<int, N>;
+
 template <int D>
 struct Geometry {
   static constexpr int ROW = D * 2;                   // bytes per K or V row in LDS
@@ -97,13 +134,13 @@ struct Geometry {
 };
 
 template <int D, int NG, int NSB>
-__global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillArgs a) {
+__global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_EXP_NW == 4) ? 2 : 1) void prefill_kernel(PrefillArgs a) {
   using Geo = Geometry<D>;
   constexpr int ROW = Geo::ROW, TILE = Geo::TILE, BUF_BYTES = Geo::BUF_BYTES;
   constexpr int NKK = D / 16;          // MFMA k-steps of the QK^T contraction
   constexpr int NMB = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;           // 16-byte pieces per row
-  constexpr int NW = NSB == 2 ? 4 : 8; // wavefronts per workgroup: 64 rows each, or 32 rows each at two per SIMD
+  constexpr int NW = NSB == 2 ? 4 : DUO_EXP_NW; // wavefronts per workgroup: 64 rows each, or 32 rows each at two per SIMD
   constexpr int WPG = NW / NG;         // wavefronts per key group
   constexpr int RW = 32 * NSB;         // query rows per wavefront
   constexpr int BM = RW * WPG;         // query rows per workgroup
@@ -112,7 +149,9 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
   const LayerView& lv = a.lv;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // in a scalar register: everything derived from it (row ranges, the mask test) stays uniform
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave / WPG, wig = wave % WPG;
   const int col = lane & 31, half = lane >> 5;
   const int peer = ((lane ^ 32) << 2);
@@ -221,28 +260,24 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
     lin_k_chunk = row * (int)ks.chunk_stride + ((slot ^ Geo::k_swz(row)) * 16);
     lin_v_chunk = row * (int)ks.chunk_stride + ((slot ^ Geo::v_swz(row)) * 16);
   }
-  auto fetch = [&](int64_t t, uint8_t* k_lds, uint8_t* v_lds) {
+  // Issue the LDS-direct loads of one tensor (K or V) of tile t into an LDS tile buffer.
+  auto fetch_one = [&](int64_t t, uint8_t* dst, auto is_v_tag) {
+    constexpr bool IS_V = decltype(is_v_tag)::value;
     const int64_t u0 = t * BN;
     const bool whole = u0 + BN <= ks.total;
     if (whole && ks.retrieval && u0 + BN <= ks.pos0) {          // dense cache rows u0 .. u0+63
-      const uint8_t* kb = ks.k_cache + u0 * ROW;
-      const uint8_t* vb = ks.v_cache + u0 * ROW;
+      const uint8_t* base = (IS_V ? ks.v_cache : ks.k_cache) + u0 * ROW;
+      const int lin = IS_V ? lin_v_cache : lin_k_cache;
 #pragma unroll
-      for (int x = 0; x < NLOAD; ++x) {
-        const int j = wig + WPG * x;
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb + x * XROWS * ROW + lin_k_cache), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb + x * XROWS * ROW + lin_v_cache), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
-      }
+      for (int x = 0; x < NLOAD; ++x)
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(base + x * XROWS * ROW + lin), LDS_PTR(void, dst + (wig + WPG * x) * 1024), 16, 0, 0);
     } else if (whole && ks.position(u0) >= ks.pos0) {           // chunk rows
       const int64_t c0 = ks.position(u0) - ks.pos0;
-      const uint8_t* kb = ks.k_chunk + c0 * ks.chunk_stride;
-      const uint8_t* vb = ks.v_chunk + c0 * ks.chunk_stride;
+      const uint8_t* base = (IS_V ? ks.v_chunk : ks.k_chunk) + c0 * ks.chunk_stride;
+      const int lin = IS_V ? lin_v_chunk : lin_k_chunk;
 #pragma unroll
-      for (int x = 0; x < NLOAD; ++x) {
-        const int j = wig + WPG * x;
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb + x * XROWS * ks.chunk_stride + lin_k_chunk), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb + x * XROWS * ks.chunk_stride + lin_v_chunk), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
-      }
+      for (int x = 0; x < NLOAD; ++x)
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(base + x * XROWS * ks.chunk_stride + lin), LDS_PTR(void, dst + (wig + WPG * x) * 1024), 16, 0, 0);
     } else {                                                    // rare: not unrolled, to keep registers free
 #pragma nounroll
       for (int x = 0; x < NLOAD; ++x) {
@@ -252,50 +287,109 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
         if (u >= ks.total) u = ks.total - 1;
         const uint8_t *kr, *vr;
         ks.rows(ks.position(u), kr, vr);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kr + ((slot ^ Geo::k_swz(row)) * 16)), LDS_PTR(void, k_lds + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vr + ((slot ^ Geo::v_swz(row)) * 16)), LDS_PTR(void, v_lds + j * 1024), 16, 0, 0);
+        const int swz = IS_V ? Geo::v_swz(row) : Geo::k_swz(row);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR((IS_V ? vr : kr) + ((slot ^ swz) * 16)), LDS_PTR(void, dst + j * 1024), 16, 0, 0);
       }
     }
   };
 
-  if (grp < n_tiles) fetch(tile_of(grp), smem + (grp * 2) * BUF_BYTES, smem + (grp * 2) * BUF_BYTES + TILE);
-  for (int it = 0; it < n_iter; ++it) {
-    const int s = it * NG + grp;
-    const bool live = s < n_tiles;
-    uint8_t* k_lds = smem + (grp * 2 + (it & 1)) * BUF_BYTES;
-    uint8_t* v_lds = k_lds + TILE;
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's loads of the tile have landed in LDS
-    __syncthreads();
-    if (s + NG < n_tiles) {
-      uint8_t* nk = smem + (grp * 2 + ((it + 1) & 1)) * BUF_BYTES;
-      fetch(tile_of(s + NG), nk, nk + TILE);
-    }
-    if (!live) continue;
-    const int64_t t = tile_of(s);
-    const int64_t ub = t * BN;
+  f32x16 s_acc[NSB][2];
+  bf16x8 pf[NSB][4];
 
-    // S^T = K Q^T : two 32-key blocks x (2 x 32) queries; each K fragment feeds both sub-blocks.
-    f32x16 s_acc[NSB][2];
+  // Per-lane LDS offsets of the operand fragments inside a tile buffer (they never change).
+  // K fragment (kb, kk): row 32 kb + col, piece (2 kk + half) ^ swizzle(col): one offset per kk,
+  // kb adds a constant.  V^T fragment (slab sl, block mb): this lane addresses key
+  // 16 sl + 4 half + e (and + 8), bytes 8 (i4 & 1) of piece (4 mb + pc0) ^ swizzle(key): one offset
+  // per mb (the swizzle does not depend on sl), sl and the + 8 rows add constants.
+  uint32_t k_frag_off[NKK], v_frag_off[NMB];
+  {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kk = 0; kk < NKK; ++kk) k_frag_off[kk] = (uint32_t)(col * ROW + (((2 * kk + half) ^ Geo::k_swz(col)) * 16));
+    const int blk = lane >> 4, l16 = lane & 15;
+    const int e = l16 >> 2, i4 = l16 & 3;
+    const int pc0 = 2 * (blk & 1) + (i4 >> 1), sub8 = (i4 & 1) * 8;
+    const int keyl = 4 * half + e;
+#pragma unroll
+    for (int mb = 0; mb < NMB; ++mb) v_frag_off[mb] = (uint32_t)(keyl * ROW + (((4 * mb + pc0) ^ Geo::v_swz(keyl)) * 16) + sub8);
+  }
+  struct VSlab { s16x4 lo[NMB], hi[NMB]; };
+  auto read_v_slab = [&](VSlab& f, const uint32_t (&va)[NMB], auto sl_tag) {
+    constexpr int SL = decltype(sl_tag)::value;
+#pragma unroll
+    for (int mb = 0; mb < NMB; ++mb) {
+      f.lo[mb] = lds_read_tr16<SL * 16 * ROW>(va[mb]);
+      f.hi[mb] = lds_read_tr16<SL * 16 * ROW + 8 * ROW>(va[mb]);
+    }
+  };
+  auto wait_v_slab = [&](VSlab& f, auto n_tag) {
+    constexpr int N = decltype(n_tag)::value;
+    if constexpr (NMB == 4) lds_wait<N>(f.lo[0], f.hi[0], f.lo[1], f.hi[1], f.lo[2], f.hi[2], f.lo[3], f.hi[3]);
+    else lds_wait<N>(f.lo[0], f.hi[0], f.lo[1], f.hi[1]);
+  };
+  auto mma_v_slab = [&](const VSlab& f, int sl) {
+#pragma unroll
+    for (int mb = 0; mb < NMB; ++mb) {
+      const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(f.lo[mb], f.hi[mb], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
       for (int sb = 0; sb < NSB; ++sb)
+        o_acc[sb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sb][sl], o_acc[sb][mb], 0, 0, 0);
+    }
+  };
+  template_int<0> i0; template_int<1> i1; template_int<2> i2; template_int<3> i3;
+  template_int<2 * NMB> i_slab;
+
+  // The matrix-core block of one iteration: O^T += V^T P^T of the previous tile (slab sl covers
+  // keys 16 sl + {4 half + t, 8 + 4 half + t}), then S^T = K Q^T of the current tile (two 32-key
+  // blocks x NSB x 32 queries; consecutive products accumulate into different registers, so none
+  // waits for the one before it).  LDS reads run one slab / two k-steps ahead of the products.
+  auto m_phase = [&](const uint8_t* v_lds, const uint8_t* k_lds, bool do_pv, bool do_qk) {
+    uint32_t va[NMB], ka[NKK];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_acc[sb][kb][r] = 0.f;
+    for (int mb = 0; mb < NMB; ++mb) va[mb] = lds_addr(v_lds) + v_frag_off[mb];
 #pragma unroll
-      for (int kk = 0; kk < NKK; ++kk) {
-        const bf16x8 kf = *(const bf16x8*)(k_lds + (32 * kb + col) * ROW + (((2 * kk + half) ^ Geo::k_swz(col)) * 16));
+    for (int kk = 0; kk < NKK; ++kk) ka[kk] = lds_addr(k_lds) + k_frag_off[kk];
+    if (do_pv) {
+      VSlab fa, fb;
+      read_v_slab(fa, va, i0);
+      read_v_slab(fb, va, i1);
+      wait_v_slab(fa, i_slab); mma_v_slab(fa, 0);
+      read_v_slab(fa, va, i2);
+      wait_v_slab(fb, i_slab); mma_v_slab(fb, 1);
+      read_v_slab(fb, va, i3);
+      wait_v_slab(fa, i_slab); mma_v_slab(fa, 2);
+      wait_v_slab(fb, i0); mma_v_slab(fb, 3);
+    }
+    if (do_qk) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb)
-          s_acc[sb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[sb][kk], s_acc[sb][kb], 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s_acc[sb][kb][r] = 0.f;
+      bf16x8 kf[NKK][2];
+      kf[0][0] = lds_read_b128<0>(ka[0]); kf[0][1] = lds_read_b128<32 * ROW>(ka[0]);
+      kf[1][0] = lds_read_b128<0>(ka[1]); kf[1][1] = lds_read_b128<32 * ROW>(ka[1]);
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        if (kk + 2 < NKK) {
+          kf[kk + 2][0] = lds_read_b128<0>(ka[kk + 2]); kf[kk + 2][1] = lds_read_b128<32 * ROW>(ka[kk + 2]);
+          lds_wait<4>(kf[kk][0], kf[kk][1]);
+        } else if (kk + 1 < NKK) {
+          lds_wait<2>(kf[kk][0], kf[kk][1]);
+        } else {
+          lds_wait<0>(kf[kk][0], kf[kk][1]);
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int sb = 0; sb < NSB; ++sb)
+            s_acc[sb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][kb], qf[sb][kk], s_acc[sb][kb], 0, 0, 0);
       }
     }
+  };
 
-    // Keep the three phases (scores, softmax, PV) apart in the instruction stream:
-    // hoisting the next phase's LDS reads over the current phase costs more
-    // registers than this kernel has at two wavefronts per SIMD.
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 pf[NSB][4];
+  // Online softmax of the tile whose first key is list entry ub: s_acc -> pf, m_i, l_i; rescales o_acc.
+  auto softmax_phase = [&](int64_t ub) {
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       // Mask (only tiles that touch the mask boundary or the end of the list).
@@ -335,14 +429,17 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
             for (int r = 0; r < 16; ++r) o_acc[sb][mb][r] *= alpha;
         }
       };
-      // Scores with the mask applied, in registers of their own: the matrix-core
-      // accumulators are only read here, never overwritten.
-      float sv[2][16];
+      if (!need_mask) {
+        // interior tile: the scores are read straight from the matrix-core accumulators
+        softmax_block([&](int kb, int r) { return s_acc[sb][kb][r]; });
+      } else {
+        // Scores with the mask applied, in registers of their own: the matrix-core
+        // accumulators are only read here, never overwritten.
+        float sv[2][16];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sv[kb][r] = s_acc[sb][kb][r];
-      if (need_mask) {
+          for (int r = 0; r < 16; ++r) sv[kb][r] = s_acc[sb][kb][r];
         const int lim = clamp_i32(ks.total - ub);
         const int qa = clamp_i32(qpos[sb] - ub);             // query position relative to the tile
         if (ks.retrieval) {
@@ -367,33 +464,53 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
               if (!vis) sv[kb][r] = -INFINITY;
             }
         }
-      }
-      softmax_block([&](int kb, int r) { return sv[kb][r]; });
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // O^T += V^T P^T.  Slab sl covers keys 16*sl + {4*half + t, 8 + 4*half + t}.
-    {
-      const int blk = lane >> 4, l16 = lane & 15;
-      const int e = l16 >> 2, i4 = l16 & 3;
-      // this lane's 8 bytes sit in piece 4*mb + pc0 of row key0 (+8), at byte (i4 & 1) * 8 of the piece
-      const int pc0 = 2 * (blk & 1) + (i4 >> 1), sub8 = (i4 & 1) * 8;
-#pragma unroll
-      for (int sl = 0; sl < 4; ++sl) {
-        const int key0 = 16 * sl + 4 * half + e;
-        const int swz = Geo::v_swz(key0);   // rows key0 and key0 + 8 share the swizzle
-#pragma unroll
-        for (int mb = 0; mb < NMB; ++mb) {
-          const int off = (((4 * mb + pc0) ^ swz) * 16) + sub8;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, v_lds + key0 * ROW + off));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, v_lds + (key0 + 8) * ROW + off));
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-          for (int sb = 0; sb < NSB; ++sb)
-            o_acc[sb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sb][sl], o_acc[sb][mb], 0, 0, 0);
-        }
+        softmax_block([&](int kb, int r) { return sv[kb][r]; });
       }
     }
+  };
+
+  // Main loop.  A wavefront's work on tile t is M_t = [O += P V of tile t-1, then S = K Q^T of
+  // tile t] (matrix cores) followed by S_t = softmax of tile t (vector unit).  The two wavefronts
+  // of every SIMD run half an iteration apart ("set B" starts one barrier interval later), so
+  // while one is in its matrix-core block the other does its softmax; a barrier ends every
+  // interval.  K runs one tile ahead of V in the LDS buffers: load L_j = (K of tile j, V of tile
+  // j-1) must have landed before interval 2j.  With one key group the eight wavefronts share the
+  // tiles, and set B issues its share of the loads in its softmax half ("B style") so that both
+  // sets have two full intervals of latency; with two key groups each set owns its tiles.
+  const bool set_b = NG == 1 ? (wave >= NW / 2) : (grp == 1);
+  const bool b_style = NG == 1 && set_b;
+  auto kbuf = [&](int j) { return smem + (grp * 2 + (j & 1)) * BUF_BYTES; };
+  auto vbuf = [&](int j) { return smem + (grp * 2 + (j & 1)) * BUF_BYTES + TILE; };
+  auto issue_l = [&](int j) {
+    const int sk = j * NG + grp, sv = (j - 1) * NG + grp;
+    if (sk < n_tiles) fetch_one(tile_of(sk), kbuf(j), std::false_type{});
+    if (j >= 1 && sv < n_tiles) fetch_one(tile_of(sv), vbuf(j - 1), std::true_type{});
+  };
+  issue_l(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's LDS-direct loads have landed
+  __builtin_amdgcn_s_barrier();
+  if (set_b) {
+    if (b_style) issue_l(1);
+    __builtin_amdgcn_s_barrier();
   }
+  for (int it = 0; it <= n_iter; ++it) {
+    const int s = it * NG + grp;
+    const bool live_qk = it < n_iter && s < n_tiles;
+    const bool live_pv = it >= 1 && s - NG < n_tiles;
+    if (!b_style) issue_l(it + 1);
+    __builtin_amdgcn_s_setprio(2);
+    m_phase(vbuf(it - 1), kbuf(it), live_pv, live_qk);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    if (b_style) issue_l(it + 2);
+    if (live_qk) softmax_phase(tile_of(s) * BN);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+  }
+  if (!set_b) __builtin_amdgcn_s_barrier();
 
   // Row sums over both lane halves.
 #pragma unroll
@@ -456,7 +573,7 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : 512) void prefill_kernel(PrefillAr
 
 template <int D, int NG, int NSB>
 hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
-  constexpr int NW = NSB == 2 ? 4 : 8;
+  constexpr int NW = NSB == 2 ? 4 : DUO_EXP_NW;
   constexpr int BM = 32 * NSB * (NW / NG);
   constexpr int lds = NG * 2 * Geometry<D>::BUF_BYTES;
   static bool configured = false;   // one attribute call per kernel instantiation and process
@@ -478,16 +595,17 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
+  constexpr int NSB = DUO_EXP_NSB;
+#ifdef DUO_EXP_NG1
+  if (a.lv.head_dim == 128) return launch_one<128, 1, NSB>(a, stream);
+  return launch_one<64, 1, NSB>(a, stream);
+#else
   // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
   const int64_t heavy_blocks = (int64_t)a.lv.batch * a.lv.n_ret * a.lv.group * ((a.n + 255) / 256);
-#ifdef DUO_EXP_NG1
-  const bool split_keys = false;
-#else
   const bool split_keys = heavy_blocks < 384;
-#endif
-  constexpr int NSB = DUO_EXP_NSB;
   if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB>(a, stream) : launch_one<128, 1, NSB>(a, stream);
   return split_keys ? launch_one<64, 2, NSB>(a, stream) : launch_one<64, 1, NSB>(a, stream);
+#endif
 }
 
 }  // namespace duo
