@@ -45,11 +45,17 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
 constexpr int BN = 64;   // keys per tile
+constexpr int kDies = 8;      // accelerator dies (XCDs), each with its own L2
+constexpr int kBundle = 32;   // workgroups per bundle = compute units per die
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ inline float swap_halves(float x, int peer_byte_addr) {
   return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(peer_byte_addr, __builtin_bit_cast(int, x)));
 }
+#ifndef DUO_EXP_PRIO_M
+#define DUO_EXP_PRIO_M 0
+#define DUO_EXP_PRIO_S 3
+#endif
 #ifndef DUO_EXP_NW
 #define DUO_EXP_NW 8
 #endif
@@ -156,8 +162,26 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   const int col = lane & 31, half = lane >> 5;
   const int peer = ((lane ^ 32) << 2);
   const int n_rb = (a.n + BM - 1) / BM;
-  const int h = lv.q_order[blockIdx.x / n_rb];
-  const int rb = n_rb - 1 - (int)(blockIdx.x % n_rb);   // longest rows first
+  // Work list.  Workgroups are dealt to the 8 accelerator dies (each with its own L2) round-robin
+  // by block index.  The work is cut into "bundles" of kBundle workgroups that read the same K/V:
+  // the G query heads of one KV head times kBundle / G neighbouring row blocks.  Bundles are
+  // ordered retrieval KV heads first, longest rows first, and dealt to the dies round-robin, so
+  // every die gets the same mix of long and short work while the workgroups running on it at any
+  // time stream the same tiles at about the same time and share them through that die's L2.
+  int h, rb;
+  {
+    const int die = (int)blockIdx.x % kDies, idx = (int)blockIdx.x / kDies;
+    const int bundle = (idx / kBundle) * kDies + die, w = idx % kBundle;
+    const int rb_per_bundle = kBundle / lv.group;
+    const int bundles_per_head = (n_rb + rb_per_bundle - 1) / rb_per_bundle;
+    if (bundle >= lv.n_kv_heads * bundles_per_head) return;
+    const int kv_slot = bundle / bundles_per_head, c = bundle % bundles_per_head;
+    const int rbi = c * rb_per_bundle + w / lv.group;
+    if (rbi >= n_rb) return;
+    const int kv = kv_slot < lv.n_ret ? lv.ret_heads[kv_slot] : lv.str_heads[kv_slot - lv.n_ret];
+    h = kv * lv.group + w % lv.group;
+    rb = n_rb - 1 - rbi;   // longest rows first
+  }
   const int b = blockIdx.y;
   const int kvh = h / lv.group;
   const uint32_t info = lv.head_info[kvh];
@@ -220,7 +244,24 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   }
   const int n_tiles = (int)(tA_end + (t_end - tB_begin));
   const int n_iter = (n_tiles + NG - 1) / NG;
-  auto tile_of = [&](int s) -> int64_t { return s < tA_end ? (int64_t)s : tB_begin + (s - tA_end); };
+  // Tile indices fit 32 bits; the per-iteration bookkeeping below is 32-bit scalar arithmetic.
+  const int tA = (int)tA_end, tB = (int)tB_begin;
+  auto tile_of = [&](int s) -> int { return s < tA ? s : tB + (s - tA); };
+  // Classes of tiles, by index: [0, t_dense_end) lie wholly in the dense cache of a retrieval head;
+  // [t_chunk_begin, t_whole_end) lie wholly in the chunk; tiles from t_whole_end on are cut by
+  // the end of the list; the others straddle regions and take the general load path.
+  const int64_t u_chunk0 = ks.n_head + (ks.pos0 - ks.tail_pos);   // list entry of the chunk's first row
+  const int t_whole_end = (int)(ks.total / BN);
+  const int t_dense_end = ks.retrieval ? (int)(ks.pos0 / BN) : 0;
+  const int t_chunk_begin = (int)((u_chunk0 + BN - 1) / BN);
+  // First tile that needs the causal mask for sub-block sb of this wavefront (retrieval heads).
+  int t_mask[NSB];
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb) {
+    const int64_t x = a.pos0 + row_w + 32 * sb - BN + 1;
+    const int64_t tm = x < 0 ? 0 : x / BN + 1;
+    t_mask[sb] = tm < t_whole_end ? (int)tm : t_whole_end;
+  }
 
   // Q^T fragments (B operand): lane (col, half) holds q[row][16*kk + 8*half .. +7].
   bf16x8 qf[NSB][NKK];
@@ -248,36 +289,39 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   // A tile whose 64 keys are consecutive rows of one region (the dense cache of a
   // retrieval head, or the chunk) is addressed as a wavefront-uniform base plus
   // per-lane offsets that never change; other tiles take the general path.
-  // (Successive loads of a wavefront are WPG * RPWL rows apart, a multiple of the
-  // swizzle period, so one set of lane offsets serves all of them.)
-  static_assert((WPG * RPWL) % CPR == 0 || (RPWL % CPR) == 0, "swizzle must not depend on the load index");
+  // (Successive loads of a wavefront are WPG * RPWL rows apart; the swizzle has period CPR rows,
+  // so a wavefront needs NPH sets of lane offsets, one per swizzle phase its loads fall in.)
   constexpr int XROWS = WPG * RPWL;    // rows between successive loads of one wavefront
-  int lin_k_cache, lin_v_cache, lin_k_chunk, lin_v_chunk;
-  {
-    const int row = wig * RPWL + lane / CPR, slot = lane % CPR;
-    lin_k_cache = row * ROW + ((slot ^ Geo::k_swz(row)) * 16);
-    lin_v_cache = row * ROW + ((slot ^ Geo::v_swz(row)) * 16);
-    lin_k_chunk = row * (int)ks.chunk_stride + ((slot ^ Geo::k_swz(row)) * 16);
-    lin_v_chunk = row * (int)ks.chunk_stride + ((slot ^ Geo::v_swz(row)) * 16);
+  constexpr int NPH = XROWS % CPR == 0 || RPWL % CPR == 0 ? 1 : CPR / XROWS;
+  static_assert(NPH == 1 || (CPR % XROWS == 0 && NLOAD % NPH == 0), "unsupported tile load geometry");
+  int lin_k_cache[NPH], lin_v_cache[NPH], lin_k_chunk[NPH], lin_v_chunk[NPH];
+#pragma unroll
+  for (int ph = 0; ph < NPH; ++ph) {
+    const int row = (wig + WPG * ph) * RPWL + lane / CPR, slot = lane % CPR;
+    lin_k_cache[ph] = row * ROW + ((slot ^ Geo::k_swz(row)) * 16);
+    lin_v_cache[ph] = row * ROW + ((slot ^ Geo::v_swz(row)) * 16);
+    lin_k_chunk[ph] = row * (int)ks.chunk_stride + ((slot ^ Geo::k_swz(row)) * 16);
+    lin_v_chunk[ph] = row * (int)ks.chunk_stride + ((slot ^ Geo::v_swz(row)) * 16);
   }
   // Issue the LDS-direct loads of one tensor (K or V) of tile t into an LDS tile buffer.
-  auto fetch_one = [&](int64_t t, uint8_t* dst, auto is_v_tag) {
+  auto fetch_one = [&](int t, uint8_t* dst, auto is_v_tag) {
     constexpr bool IS_V = decltype(is_v_tag)::value;
-    const int64_t u0 = t * BN;
-    const bool whole = u0 + BN <= ks.total;
-    if (whole && ks.retrieval && u0 + BN <= ks.pos0) {          // dense cache rows u0 .. u0+63
+    const int64_t u0 = (int64_t)t * BN;
+    if (t < t_dense_end) {                                      // dense cache rows u0 .. u0+63
       const uint8_t* base = (IS_V ? ks.v_cache : ks.k_cache) + u0 * ROW;
-      const int lin = IS_V ? lin_v_cache : lin_k_cache;
 #pragma unroll
-      for (int x = 0; x < NLOAD; ++x)
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(base + x * XROWS * ROW + lin), LDS_PTR(void, dst + (wig + WPG * x) * 1024), 16, 0, 0);
-    } else if (whole && ks.position(u0) >= ks.pos0) {           // chunk rows
-      const int64_t c0 = ks.position(u0) - ks.pos0;
+      for (int x = 0; x < NLOAD; ++x) {
+        const int lin = IS_V ? lin_v_cache[x % NPH] : lin_k_cache[x % NPH];
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(base + (x / NPH) * (NPH * XROWS * ROW) + lin), LDS_PTR(void, dst + (wig + WPG * x) * 1024), 16, 0, 0);
+      }
+    } else if (t >= t_chunk_begin && t < t_whole_end) {         // chunk rows
+      const int64_t c0 = u0 - u_chunk0;
       const uint8_t* base = (IS_V ? ks.v_chunk : ks.k_chunk) + c0 * ks.chunk_stride;
-      const int lin = IS_V ? lin_v_chunk : lin_k_chunk;
 #pragma unroll
-      for (int x = 0; x < NLOAD; ++x)
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(base + x * XROWS * ks.chunk_stride + lin), LDS_PTR(void, dst + (wig + WPG * x) * 1024), 16, 0, 0);
+      for (int x = 0; x < NLOAD; ++x) {
+        const int lin = IS_V ? lin_v_chunk[x % NPH] : lin_k_chunk[x % NPH];
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(base + (x / NPH) * (NPH * XROWS * ks.chunk_stride) + lin), LDS_PTR(void, dst + (wig + WPG * x) * 1024), 16, 0, 0);
+      }
     } else {                                                    // rare: not unrolled, to keep registers free
 #pragma nounroll
       for (int x = 0; x < NLOAD; ++x) {
@@ -389,12 +433,12 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   };
 
   // Online softmax of the tile whose first key is list entry ub: s_acc -> pf, m_i, l_i; rescales o_acc.
-  auto softmax_phase = [&](int64_t ub) {
+  auto softmax_phase = [&](int t) {
+    const int64_t ub = (int64_t)t * BN;
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       // Mask (only tiles that touch the mask boundary or the end of the list).
-      const int64_t sb_qpos0 = a.pos0 + row_w + 32 * sb;
-      const bool need_mask = !ks.retrieval || (ub + BN - 1 > sb_qpos0) || (ub + BN > ks.total);
+      const bool need_mask = !ks.retrieval || t >= t_mask[sb];
       // Online softmax for this lane's query column; `score(kb, r)` yields the masked score.
       auto softmax_block = [&](auto&& score) {
         float mx = -INFINITY;
@@ -477,7 +521,10 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   // j-1) must have landed before interval 2j.  With one key group the eight wavefronts share the
   // tiles, and set B issues its share of the loads in its softmax half ("B style") so that both
   // sets have two full intervals of latency; with two key groups each set owns its tiles.
-  const bool set_b = NG == 1 ? (wave >= NW / 2) : (grp == 1);
+  // (With one wavefront per SIMD - 64 rows each - there is nothing to alternate with: all
+  // wavefronts run in phase and one barrier per iteration publishes the loads.)
+  constexpr bool kPingPong = NW == 8;
+  const bool set_b = kPingPong && (NG == 1 ? (wave >= NW / 2) : (grp == 1));
   const bool b_style = NG == 1 && set_b;
   auto kbuf = [&](int j) { return smem + (grp * 2 + (j & 1)) * BUF_BYTES; };
   auto vbuf = [&](int j) { return smem + (grp * 2 + (j & 1)) * BUF_BYTES + TILE; };
@@ -498,19 +545,21 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
     const bool live_qk = it < n_iter && s < n_tiles;
     const bool live_pv = it >= 1 && s - NG < n_tiles;
     if (!b_style) issue_l(it + 1);
-    __builtin_amdgcn_s_setprio(2);
+    __builtin_amdgcn_s_setprio(DUO_EXP_PRIO_M);
     m_phase(vbuf(it - 1), kbuf(it), live_pv, live_qk);
-    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_s_setprio(DUO_EXP_PRIO_S);
     __builtin_amdgcn_sched_barrier(0);
-    if (b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
-    __builtin_amdgcn_s_barrier();
-    if (b_style) issue_l(it + 2);
-    if (live_qk) softmax_phase(tile_of(s) * BN);
+    if constexpr (kPingPong) {
+      if (b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
+      __builtin_amdgcn_s_barrier();
+      if (b_style) issue_l(it + 2);
+    }
+    if (live_qk) softmax_phase(tile_of(s));
     __builtin_amdgcn_sched_barrier(0);
     if (!b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
   }
-  if (!set_b) __builtin_amdgcn_s_barrier();
+  if (kPingPong && !set_b) __builtin_amdgcn_s_barrier();
 
   // Row sums over both lane halves.
 #pragma unroll
@@ -583,7 +632,9 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
     configured = true;
   }
   const int n_rb = (a.n + BM - 1) / BM;
-  dim3 grid((unsigned)(n_rb * a.lv.n_q_heads), a.lv.batch);
+  const int rb_per_bundle = kBundle / a.lv.group;
+  const int bundles = a.lv.n_kv_heads * ((n_rb + rb_per_bundle - 1) / rb_per_bundle);
+  dim3 grid((unsigned)((bundles + kDies - 1) / kDies * kDies * kBundle), a.lv.batch);
   prefill_kernel<D, NG, NSB><<<grid, NW * 64, lds, stream>>>(a);
   return hipGetLastError();
 }
