@@ -25,8 +25,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, scaled by a 1 GiB
-# device copy (summary under profiles/); known for the default workload only.
-MEASURED_TRAFFIC = {"c2": {"decode": 138.98e6 + 0.18e6, "prefill": 780.4e6 + 34.5e6}}
+# device copy (summaries under profiles/); known for these workloads only.
+MEASURED_TRAFFIC = {"c2": {"decode": 139.14e6 + 0.17e6, "prefill": 172.2e6 + 40.8e6},
+                    "c4": {"decode": 2149.2e6 + 0.6e6}}
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
