@@ -239,7 +239,8 @@ def main():
         roof_dec = {"bound": "hbm", "achieved": round(dec_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
                     "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("decode"),
-                    "kernel": "duo::decode_kernel", "bytes_per_launch": int(avg_dec_bytes),
+                    "kernel": "duo::decode_kernel" if (group == 1 and not kv_dtype) else "duo::decode_sk_kernel",
+                    "bytes_per_launch": int(avg_dec_bytes),
                     "avg_launch_us": round(dec_call_us, 2)}
     roof_pre = None
     if pre_tflops:
