@@ -1,18 +1,20 @@
-// Decode attention: one query per sequence against the split KV cache
-// (paper, Section 2.3, Decoding; attention definitions of Section 2.2).
+// Decode attention on the vector unit: one query per sequence against the split KV
+// cache (paper, Section 2.3, Decoding; attention definitions of Section 2.2).
+// This kernel serves one query head per KV head on a bf16 cache (its templates
+// also cover query groups and fp8 rows, which the matrix-core kernel in
+// kernels_decode_sk.hip handles with far fewer instructions per byte).
 //
 // The step is bound by HBM bandwidth: every cached K and V row of a retrieval
 // head is read once per token, while a streaming head reads at most
 // sink + recent rows.  Work decomposition:
 //   - one work item (workgroup) per (sequence, retrieval KV head, key split) and
-//     one per (sequence, streaming KV head); all query heads of a GQA group share
-//     the item, so K/V are read once per group;
-//   - inside an item the head_dim/8 (bf16) or head_dim/16 (fp8) lanes of a "row
-//     group" each own one 16-byte piece of a row, so a wavefront load covers
-//     1 KiB of consecutive cache memory; loads are double-buffered in registers
-//     so the next rows are in flight while the current ones are consumed; each
-//     row group keeps its own running (max, sum, output) softmax state, merged
-//     once at the end of the item;
+//     one per (sequence, streaming KV head);
+//   - inside an item the head_dim/8 lanes of a "row group" each own one 16-byte
+//     piece of a row, so a wavefront load covers 1 KiB of consecutive cache
+//     memory; two register buffers of loads alternate, the next one being issued
+//     before the current one is consumed, and the very first loads go out before
+//     the query is read; each row group keeps its own running (max, sum, output)
+//     softmax state, merged once at the end of the item;
 //   - the split partials of a head are merged by the last workgroup of that head
 //     to finish (an integer ticket per head decides who is last; the merge order
 //     is fixed, so results are deterministic) - one launch per token;

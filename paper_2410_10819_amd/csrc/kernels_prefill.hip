@@ -4,23 +4,27 @@
 // (sink tokens + a window of `recent` positions ending at the query), so K/V
 // tiles outside the mask are never loaded.
 //
-// Flash-style kernel for CDNA4.  A workgroup of four wavefronts owns a block of
-// query rows of one query head; every wavefront owns 64 rows (two 32-row
-// sub-blocks, so each K/V fragment read from LDS feeds two MFMAs and the softmax
-// arithmetic of one sub-block can overlap the matrix work of the other).  The
-// wavefronts form NG "key groups": with NG = 1 all four share each 64-key K/V
-// tile (256 rows per workgroup); with NG = 2 the two groups take alternate tiles
-// of the same 128 rows and their partial results are merged through LDS at the
-// end, which doubles the number of workgroups when a chunk has few row blocks.
-// K/V tiles are loaded straight from global memory into LDS (the lane-ordered
-// LDS-direct load; rows are stored with their 16-byte pieces XOR-swizzled so the
-// fragment reads are free of bank conflicts), double-buffered, the next tile's
-// loads being in flight while the current tile is computed.  Both contractions
-// use the bf16 MFMA 32x32x16 with fp32 accumulation; the softmax is online, in
-// registers.  The score tile is produced transposed (S^T = K Q^T) so that each
-// lane owns one query column: row statistics need one cross-lane exchange, and
-// the accumulator registers of S^T are, after conversion to bf16, exactly the B
-// operand of O^T += V^T P^T.  V^T fragments come from LDS transpose reads.
+// Flash-style kernel for CDNA4.  A workgroup of eight wavefronts owns a block of
+// query rows of one query head; every wavefront owns 32 rows and two wavefronts
+// share a SIMD.  The wavefronts form NG "key groups": with NG = 1 all eight share
+// each 64-key K/V tile (256 rows per workgroup); with NG = 2 the two groups take
+// alternate tiles of the same 128 rows and their partial results are merged
+// through LDS at the end, which doubles the number of workgroups when a chunk has
+// few row blocks.  K/V tiles are loaded straight from global memory into LDS (the
+// lane-ordered LDS-direct load; rows are stored with their 16-byte pieces
+// XOR-swizzled so the fragment reads are free of bank conflicts), K one tile
+// ahead of V, the next tile's loads being in flight while the current tile is
+// computed.  Both contractions use the bf16 MFMA 32x32x16 with fp32 accumulation;
+// the softmax is online, in registers.  The score tile is produced transposed
+// (S^T = K Q^T) so that each lane owns one query column: row statistics need one
+// cross-lane exchange, and the accumulator registers of S^T are, after conversion
+// to bf16, exactly the B operand of O^T += V^T P^T.  V^T fragments come from LDS
+// transpose reads.  A wavefront alternates a matrix-core block (PV of the previous
+// tile, QK^T of the current one, operand reads pipelined ahead of the products)
+// with the softmax of the current tile; the two wavefronts of a SIMD run half an
+// iteration apart.  (On this part matrix-core and vector-unit instructions of the
+// two wavefronts do not overlap in time - the phases add up - so what counts is
+// the instruction count of the softmax and of the bookkeeping around it.)
 //
 // Keys are addressed through a "virtual key list" so that both head classes
 // share the code: for a retrieval head it is positions 0 .. pos0+n-1 (cache
