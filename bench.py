@@ -73,6 +73,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--splits", type=int, default=0, help="key splits per retrieval head in decode (0 = automatic)")
+    ap.add_argument("--sweep", default=None, choices=["decode_ratio", "decode_context", "prefill_chunk"],
+                    help="instead of the benchmark line, print one JSON line per point of a sweep that mirrors "
+                         "the shape of the paper's efficiency figures (latency against retrieval-head ratio, "
+                         "context length, pre-filling chunk size), each with the all-retrieval (= full "
+                         "attention) run through the same kernels beside it")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -88,6 +93,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     lib = duo.load()                      # raises if the HIP library is missing: no fallback
+    if args.sweep:
+        run_sweep(args.sweep, torch, duo, synth, lib, args.seed)
+        return
     w = WORKLOADS[args.workload]
     hq, hkv, d, B = w["hq"], w["hkv"], w["d"], w["batch"]
     sink, recent = w["sink"], w["recent"]
@@ -276,6 +284,90 @@ def main():
     }
     duo.duo_cache_destroy(handle)
     print(json.dumps(result))
+
+
+def run_sweep(name, torch, duo, synth, lib, seed):
+    """Latency sweeps on synthetic layers of the paper's two shapes (Section 3.4 and its figures on decoding
+    and pre-filling efficiency): MHA = 32 heads x 128 (Llama-2-7B-shaped), GQA = 32 query / 8 KV heads x 128
+    (Llama-3-8B-shaped); sink 64, recent 256.  Every point is also run with all heads retrieval, which is
+    full attention through the same kernels, and the ratio of the two times is reported."""
+    sink, recent, d = 64, 256, 128
+    table = torch.from_numpy(synth.normal_table_bf16().view(np.int16)).cuda()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def fill(tensor_id, heads, pos, n_pos):
+        t = torch.empty((1, n_pos, heads, d), dtype=torch.bfloat16, device="cuda")
+        duo.duo_synth_fill_bf16(t[0], table, synth.stream_key(seed, 0, tensor_id, 0), pos, n_pos, heads, d)
+        return t
+
+    def timed(fn, iters):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def decode_us(hq, hkv, n_ret, n_ctx):
+        mask = np.zeros((1, hkv), dtype=np.uint8)
+        mask[0, np.random.default_rng(seed).permutation(hkv)[:n_ret]] = 1
+        h = duo.duo_cache_create(1, 1, hq, hkv, d, sink, recent, n_ctx + 1, mask)
+        for p in range(0, n_ctx, 1 << 16):
+            n = min(1 << 16, n_ctx - p)
+            duo.duo_kv_append(h, 0, fill(synth.TENSOR_K, hkv, p, n), fill(synth.TENSOR_V, hkv, p, n), n)
+        q = fill(synth.TENSOR_Q, hq, n_ctx, 1)
+        o = torch.empty_like(q)
+        ms = timed(lambda: lib.duo_attn_decode(h, 0, q.data_ptr(), None, None, None, o.data_ptr(), None, stream), 50)
+        duo.duo_cache_destroy(h)
+        return ms * 1e3
+
+    def prefill_ms(hq, hkv, n_ret, n_ctx, chunk):
+        mask = np.zeros((1, hkv), dtype=np.uint8)
+        mask[0, np.random.default_rng(seed).permutation(hkv)[:n_ret]] = 1
+        h = duo.duo_cache_create(1, 1, hq, hkv, d, sink, recent, n_ctx, mask)
+        out = torch.empty((1, chunk, hq, d), dtype=torch.bfloat16, device="cuda")
+        total = 0.0
+        for p in range(0, n_ctx, chunk):
+            n = min(chunk, n_ctx - p)
+            q, k, v = fill(synth.TENSOR_Q, hq, p, n), fill(synth.TENSOR_K, hkv, p, n), fill(synth.TENSOR_V, hkv, p, n)
+            total += timed(lambda: lib.duo_attn_prefill(h, 0, q.data_ptr(), k.data_ptr(), v.data_ptr(), n, None,
+                                                        out.data_ptr(), None, stream), 1)
+            duo.duo_kv_append(h, 0, k, v, n)
+        duo.duo_cache_destroy(h)
+        return total
+
+    shapes = {"mha": (32, 32), "gqa": (32, 8)}
+    if name == "decode_ratio":
+        for shape, n_ctx in (("mha", 32768), ("gqa", 131072)):
+            hq, hkv = shapes[shape]
+            full = decode_us(hq, hkv, hkv, n_ctx)
+            for n_ret in sorted({0, hkv // 8, hkv // 4, 3 * hkv // 8, hkv // 2, 3 * hkv // 4, hkv}):
+                us = full if n_ret == hkv else decode_us(hq, hkv, n_ret, n_ctx)
+                print(json.dumps({"sweep": name, "shape": shape, "context": n_ctx, "retrieval_ratio": n_ret / hkv,
+                                  "decode_us": round(us, 2), "full_attention_us": round(full, 2),
+                                  "speedup_vs_full": round(full / us, 3)}), flush=True)
+    elif name == "decode_context":
+        for shape, n_ret, ctxs in (("mha", 8, (8192, 16384, 32768, 65536, 131072, 262144)),
+                                   ("gqa", 4, (32768, 131072, 524288, 1048576))):
+            hq, hkv = shapes[shape]
+            for n_ctx in ctxs:
+                us, full = decode_us(hq, hkv, n_ret, n_ctx), decode_us(hq, hkv, hkv, n_ctx)
+                print(json.dumps({"sweep": name, "shape": shape, "context": n_ctx, "retrieval_ratio": n_ret / hkv,
+                                  "decode_us": round(us, 2), "full_attention_us": round(full, 2),
+                                  "speedup_vs_full": round(full / us, 3)}), flush=True)
+    else:
+        for shape, n_ret, n_ctx, chunks in (("mha", 8, 102400, (4096, 8192, 16384, 32768, 102400)),
+                                            ("gqa", 4, 327680, (16384, 32768, 65536, 163840))):
+            hq, hkv = shapes[shape]
+            for chunk in chunks:
+                ms, full = prefill_ms(hq, hkv, n_ret, n_ctx, chunk), prefill_ms(hq, hkv, hkv, n_ctx, chunk)
+                print(json.dumps({"sweep": name, "shape": shape, "context": n_ctx, "chunk": chunk,
+                                  "retrieval_ratio": n_ret / hkv, "prefill_ms": round(ms, 2),
+                                  "full_attention_ms": round(full, 2), "speedup_vs_full": round(full / ms, 3)}),
+                      flush=True)
 
 
 def cpu_baseline(synth, seed, w, mask, n_ctx, batch):
