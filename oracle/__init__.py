@@ -12,6 +12,8 @@ from .duo_oracle import (  # noqa: F401
     R_INCLUDES_SELF,
     visible_mask,
     visible_count,
+    visible_mask_deployed,
+    prefill_chunk_deployed,
     attention_rows,
     prefill_chunk,
     decode_step,

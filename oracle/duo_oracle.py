@@ -17,7 +17,8 @@ Readings taken where the paper is silent (each is listed in the design notes):
     positions i-R+1 .. i (flip R_INCLUDES_SELF for the other reading);
   * sink set and window are united; nothing is visible beyond position i;
   * in chunked pre-filling a streaming query sees exactly the Lambda mask,
-    independent of the chunk size;
+    independent of the chunk size; the deployment text's variant (causal attention
+    over [pruned cache || chunk]) is a second mode, visible_mask_deployed;
   * query head h uses KV head h // (Hq / Hkv).
 
 Parity pins (tests/test_oracle_*.py): pure-Python brute force on tiny inputs
@@ -59,8 +60,25 @@ def visible_count(i: int, sink: int, recent: int, retrieval: bool) -> int:
     return int(visible_mask(i, sink, recent, retrieval).sum())
 
 
-def attention_rows(q, k_hist, v_hist, positions, retrieval_mask, sink, recent, scale=None):
+def visible_mask_deployed(i: int, pos0: int, sink: int, recent: int, retrieval: bool) -> np.ndarray:
+    """Which keys 0..i the query at position i sees when its chunk starts at position pos0 and the
+    streaming heads run plain causal attention over [pruned cache || chunk], as the deployment
+    text of Section 2.3 (Chunked Pre-filling) describes it: the cache pruned after the previous
+    chunk holds the sink tokens and the last `recent` tokens before pos0, and every earlier token
+    of the query's own chunk is visible.  Unlike the Lambda mask this depends on where the chunk
+    starts.  Retrieval heads: causal, as always.
+    """
+    assert 0 <= pos0 <= i
+    j = np.arange(i + 1)
+    if retrieval:
+        return np.ones(i + 1, dtype=bool)
+    return (j < sink) | (j >= pos0 - recent)
+
+
+def attention_rows(q, k_hist, v_hist, positions, retrieval_mask, sink, recent, scale=None, chunk_starts=None):
     """Attention of some queries of one sequence against the full K/V history.
+    With chunk_starts (one chunk start per query) the streaming heads use the deployed
+    chunk-causal visibility (visible_mask_deployed) instead of the Lambda mask.
 
     q            [n, Hq, D]   float64, query vectors
     k_hist/v_hist[T, Hkv, D]  float64, keys/values of positions 0..T-1
@@ -87,7 +105,10 @@ def attention_rows(q, k_hist, v_hist, positions, retrieval_mask, sink, recent, s
         assert 0 <= i < k_hist.shape[0]
         for h in range(hq):
             g = h // group
-            vis = visible_mask(i, sink, recent, bool(retrieval_mask[g]))
+            if chunk_starts is None:
+                vis = visible_mask(i, sink, recent, bool(retrieval_mask[g]))
+            else:
+                vis = visible_mask_deployed(i, int(chunk_starts[r]), sink, recent, bool(retrieval_mask[g]))
             keys = k_hist[: i + 1, g, :][vis]
             vals = v_hist[: i + 1, g, :][vis]
             s = scale * (keys @ q[r, h])
@@ -108,6 +129,13 @@ def prefill_chunk(q_chunk, k_hist, v_hist, pos0, retrieval_mask, sink, recent, s
     n = q_chunk.shape[0]
     return attention_rows(q_chunk, k_hist, v_hist, np.arange(pos0, pos0 + n),
                           retrieval_mask, sink, recent, scale)
+
+
+def prefill_chunk_deployed(q_chunk, k_hist, v_hist, pos0, retrieval_mask, sink, recent, scale=None):
+    """One pre-filling chunk with the deployed (chunk-causal) streaming attention of Section 2.3."""
+    n = q_chunk.shape[0]
+    return attention_rows(q_chunk, k_hist, v_hist, np.arange(pos0, pos0 + n), retrieval_mask, sink, recent, scale,
+                          chunk_starts=np.full(n, pos0))
 
 
 def decode_step(q_tok, k_hist, v_hist, retrieval_mask, sink, recent, scale=None):

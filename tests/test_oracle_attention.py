@@ -268,3 +268,70 @@ def test_merge_partials_equals_unsplit():
         mo, mlse = oracle.merge_partials(ms, ls, np.array(os_))
         np.testing.assert_allclose(mo, o[0], atol=1e-14)
         assert mlse == pytest.approx(lse[0], abs=1e-13)
+
+
+# ---- the deployment text's streaming pre-filling (causal attention over [pruned cache || chunk])
+
+def _brute_deployed_visible(i, pos0, sink, recent, cache_model_positions):
+    """Visibility derived from the mechanism: what the cache held when the chunk started, plus the
+    chunk's own earlier tokens."""
+    return sorted(set(cache_model_positions) | set(range(pos0, i + 1)))
+
+
+def test_deployed_mask_equals_cache_contents_plus_own_chunk():
+    # the streaming cache after the previous chunks (oracle.CacheModel, written from the eviction
+    # rule) is what the next chunk's queries see, together with their chunk's earlier tokens
+    for sink, recent, chunks in ((1, 2, [4, 4, 4, 4]), (3, 5, [7, 1, 9, 2, 6]), (0, 4, [3, 3, 3]), (4, 2, [2, 2, 2, 2])):
+        model = oracle.CacheModel(sink, recent, retrieval=False)
+        pos0 = 0
+        for n in chunks:
+            held = model.positions()
+            for i in range(pos0, pos0 + n):
+                want = _brute_deployed_visible(i, pos0, sink, recent, held)
+                got = np.flatnonzero(oracle.visible_mask_deployed(i, pos0, sink, recent, False)).tolist()
+                assert got == want, (sink, recent, pos0, i)
+            for _ in range(n):
+                model.append(np.zeros(1), np.zeros(1))
+            pos0 += n
+
+
+def test_deployed_mask_figure_case_counts():
+    # figure "Decoding and Chunked Pre-filling": one sink, two recent tokens, chunks of 4: the r-th query
+    # of chunk c >= 1 sees the 3 cached tokens {0, 4c-2, 4c-1} and r + 1 tokens of its chunk
+    for c in range(1, 4):
+        for r in range(4):
+            vis = np.flatnonzero(oracle.visible_mask_deployed(4 * c + r, 4 * c, 1, 2, False)).tolist()
+            assert vis == [0, 4 * c - 2, 4 * c - 1] + list(range(4 * c, 4 * c + r + 1))
+
+
+def test_deployed_special_cases():
+    rng = np.random.default_rng(5)
+    t, hq, hkv, d = 40, 4, 2, 8
+    q, k, v = rng.standard_normal((t, hq, d)), rng.standard_normal((t, hkv, d)), rng.standard_normal((t, hkv, d))
+    mask = np.array([0, 0])
+    # one chunk over the whole sequence: plain causal attention for every head
+    o1, l1 = oracle.prefill_chunk_deployed(q, k, v, 0, mask, 2, 3)
+    o2, l2 = oracle.attention_rows(q, k, v, np.arange(t), np.array([1, 1]), 2, 3)
+    assert np.allclose(o1, o2, atol=1e-12) and np.allclose(l1, l2, atol=1e-12)
+    # chunks of one token: the Lambda mask with a window of recent + 1 positions
+    o3 = np.concatenate([oracle.prefill_chunk_deployed(q[i:i + 1], k[:i + 1], v[:i + 1], i, mask, 2, 3)[0] for i in range(t)])
+    o4, _ = oracle.attention_rows(q, k, v, np.arange(t), mask, 2, 4)
+    assert np.allclose(o3, o4, atol=1e-12)
+    # retrieval heads are untouched by the mode
+    mix = np.array([1, 0])
+    o5, _ = oracle.prefill_chunk_deployed(q[20:], k, v, 20, mix, 2, 3)
+    o6, _ = oracle.attention_rows(q[20:], k, v, np.arange(20, t), mix, 2, 3)
+    assert np.allclose(o5[:, :2], o6[:, :2], atol=1e-12) and not np.allclose(o5[:, 2:], o6[:, 2:], atol=1e-6)
+
+
+def test_deployed_one_hot_probe_counts():
+    # Q = 0 -> uniform weights: output of a one-hot V column is 1 / |Vis| on visible keys
+    t, sink, recent, pos0 = 30, 2, 4, 17
+    q = np.zeros((t - pos0, 1, 4)); k = np.random.default_rng(1).standard_normal((t, 1, 4))
+    for jstar in (0, 1, 2, 12, 13, 16, 17, 25):
+        v = np.zeros((t, 1, 4)); v[jstar, 0, 0] = 1.0
+        o, _ = oracle.prefill_chunk_deployed(q, k, v, pos0, np.array([0]), sink, recent)
+        for r, i in enumerate(range(pos0, t)):
+            n_vis = min(sink, pos0) + min(recent, pos0 - min(sink, pos0)) + (i - pos0 + 1)
+            seen = jstar <= i and (jstar < sink or jstar >= pos0 - recent)
+            assert abs(o[r, 0, 0] - (1.0 / n_vis if seen else 0.0)) < 1e-12
