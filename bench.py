@@ -324,7 +324,8 @@ def run_sweep(name, torch, duo, synth, lib, seed):
         duo.duo_cache_destroy(h)
         return ms * 1e3
 
-    def prefill_ms(hq, hkv, n_ret, n_ctx, chunk):
+    def prefill_ms(hq, hkv, n_ret, n_ctx, chunk, deployed=False):
+        call = lib.duo_attn_prefill_deployed if deployed else lib.duo_attn_prefill
         mask = np.zeros((1, hkv), dtype=np.uint8)
         mask[0, np.random.default_rng(seed).permutation(hkv)[:n_ret]] = 1
         h = duo.duo_cache_create(1, 1, hq, hkv, d, sink, recent, n_ctx, mask)
@@ -333,8 +334,8 @@ def run_sweep(name, torch, duo, synth, lib, seed):
         for p in range(0, n_ctx, chunk):
             n = min(chunk, n_ctx - p)
             q, k, v = fill(synth.TENSOR_Q, hq, p, n), fill(synth.TENSOR_K, hkv, p, n), fill(synth.TENSOR_V, hkv, p, n)
-            total += timed(lambda: lib.duo_attn_prefill(h, 0, q.data_ptr(), k.data_ptr(), v.data_ptr(), n, None,
-                                                        out.data_ptr(), None, stream), 1)
+            total += timed(lambda: call(h, 0, q.data_ptr(), k.data_ptr(), v.data_ptr(), n, None, out.data_ptr(), None,
+                                        stream), 1)
             duo.duo_kv_append(h, 0, k, v, n)
         duo.duo_cache_destroy(h)
         return total
@@ -364,10 +365,12 @@ def run_sweep(name, torch, duo, synth, lib, seed):
             hq, hkv = shapes[shape]
             for chunk in chunks:
                 ms, full = prefill_ms(hq, hkv, n_ret, n_ctx, chunk), prefill_ms(hq, hkv, hkv, n_ctx, chunk)
+                dep = prefill_ms(hq, hkv, n_ret, n_ctx, chunk, deployed=True)
                 print(json.dumps({"sweep": name, "shape": shape, "context": n_ctx, "chunk": chunk,
                                   "retrieval_ratio": n_ret / hkv, "prefill_ms": round(ms, 2),
-                                  "full_attention_ms": round(full, 2), "speedup_vs_full": round(full / ms, 3)}),
-                      flush=True)
+                                  "deployed_chunk_causal_ms": round(dep, 2), "full_attention_ms": round(full, 2),
+                                  "speedup_vs_full": round(full / ms, 3),
+                                  "deployed_speedup_vs_full": round(full / dep, 3)}), flush=True)
 
 
 def cpu_baseline(synth, seed, w, mask, n_ctx, batch):

@@ -115,6 +115,16 @@ int duo_attn_prefill(duo_cache_t* cache, int layer, const void* q, const void* k
                      const void* v, int n_new, const duo_call_params_t* params,
                      void* out, float* lse, void* stream);
 
+/* The same call with the streaming heads' attention as the paper deploys it (Section 2.3,
+ * Chunked Pre-filling): plain causal attention over [pruned streaming cache || chunk], i.e. a
+ * streaming query sees the sink tokens, the `recent` tokens the cache retained when the chunk
+ * started, and every earlier token of its own chunk.  The result depends on where the chunks
+ * start (a chunk of the whole sequence is full attention; chunks of one token give a Lambda mask
+ * of recent + 1 positions).  Retrieval heads, arguments and errors as duo_attn_prefill. */
+int duo_attn_prefill_deployed(duo_cache_t* cache, int layer, const void* q, const void* k,
+                              const void* v, int n_new, const duo_call_params_t* params,
+                              void* out, float* lse, void* stream);
+
 /* One decoding step (Section 2.3, Decoding).  q: [batch, 1, n_q_heads, head_dim].
  * If k and v are NULL the new token has already been appended and the query sits
  * at position len-1.  If both are given ([batch, 1, n_kv_heads, head_dim]) they

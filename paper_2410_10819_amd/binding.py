@@ -64,6 +64,7 @@ def load() -> ctypes.CDLL:
     lib.duo_set_decode_kernel.argtypes = [vp, i32]
     lib.duo_kv_append.argtypes = [vp, i32, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp]
     lib.duo_attn_prefill.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
+    lib.duo_attn_prefill_deployed.argtypes = lib.duo_attn_prefill.argtypes
     lib.duo_attn_decode.argtypes = [vp, i32, vp, vp, vp, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
     lib.duo_decode_step.argtypes = lib.duo_attn_decode.argtypes
     lib.duo_cache_export.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, ctypes.POINTER(i64), vp]
@@ -184,6 +185,14 @@ def duo_attn_prefill(cache, layer, q, k, v, n_new, out, lse=None, params=None, s
     _check(load().duo_attn_prefill(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
                                    _ptr(v, "v", torch.bfloat16), n_new, pp, _ptr(out, "out", torch.bfloat16),
                                    _ptr(lse, "lse", torch.float32), _stream(stream)))
+
+
+def duo_attn_prefill_deployed(cache, layer, q, k, v, n_new, out, lse=None, params=None, stream=None):
+    import torch
+    pp, keep = _params(params)
+    _check(load().duo_attn_prefill_deployed(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
+                                            _ptr(v, "v", torch.bfloat16), n_new, pp, _ptr(out, "out", torch.bfloat16),
+                                            _ptr(lse, "lse", torch.float32), _stream(stream)))
 
 
 def duo_attn_decode(cache, layer, q, out, k=None, v=None, lse=None, params=None, stream=None):

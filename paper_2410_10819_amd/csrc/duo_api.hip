@@ -306,8 +306,8 @@ int duo_kv_append(duo_cache_t* c, int layer, const void* k, const void* v, int n
   return DUO_OK;
 }
 
-int duo_attn_prefill(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
-                     int n_new, const duo_call_params_t* params, void* out, float* lse, void* stream) {
+static int prefill_common(duo_cache_t* c, int layer, const void* q, const void* k, const void* v, int n_new,
+                          const duo_call_params_t* params, void* out, float* lse, void* stream, bool chunk_causal) {
   int rc = check_handle_layer(c, layer);
   if (rc != DUO_OK) return rc;
   if (!q || !k || !v || !out) return fail(DUO_EINVAL, "q, k, v and out must not be NULL");
@@ -321,9 +321,20 @@ int duo_attn_prefill(duo_cache_t* c, int layer, const void* q, const void* k, co
     return fail(DUO_EINVAL, "duo_attn_prefill supports bf16 caches only");
   duo::PrefillArgs a;
   a.lv = L.view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
+  a.chunk_causal = chunk_causal ? 1 : 0;
   hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "prefill launch");
   return DUO_OK;
+}
+
+int duo_attn_prefill(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                     int n_new, const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  return prefill_common(c, layer, q, k, v, n_new, params, out, lse, stream, false);
+}
+
+int duo_attn_prefill_deployed(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                              int n_new, const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  return prefill_common(c, layer, q, k, v, n_new, params, out, lse, stream, true);
 }
 
 static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,

@@ -74,6 +74,7 @@ struct PrefillArgs {
   float* lse;          // [batch][n_q_heads][n] or null
   int64_t pos0;        // tokens in the cache = position of the chunk's first query
   int32_t n;           // chunk length
+  int32_t chunk_causal;  // streaming heads: causal attention over [retained cache || chunk] instead of the Lambda mask
 };
 
 hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int64_t pos0,

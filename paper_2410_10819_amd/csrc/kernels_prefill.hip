@@ -230,10 +230,15 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
     qpos[sb] = a.pos0 + c;
   }
 
+  // A list that is attended causally as a whole: every retrieval head, and a streaming head in
+  // the deployed chunk-causal mode (causal attention over [retained cache || chunk]).  The list
+  // entry of a chunk position p is p - gap.
+  const bool causal_list = ks.retrieval || a.chunk_causal != 0;
+  const int64_t gap = ks.tail_pos - ks.n_head;
   // Tile list of the workgroup: [0, tA_end) covers the sink part, [tB_begin, t_end) the window.
   int64_t tA_end, tB_begin, t_end;
-  if (ks.retrieval) {
-    tA_end = 0; tB_begin = 0; t_end = qpos_last / BN + 1;
+  if (causal_list) {
+    tA_end = 0; tB_begin = 0; t_end = (qpos_last - gap) / BN + 1;
   } else {
     const int64_t usink = (int64_t)lv.sink < qpos_last + 1 ? lv.sink : qpos_last + 1;
     tA_end = (usink + BN - 1) / BN;
@@ -258,11 +263,11 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   const int t_whole_end = (int)(ks.total / BN);
   const int t_dense_end = ks.retrieval ? (int)(ks.pos0 / BN) : 0;
   const int t_chunk_begin = (int)((u_chunk0 + BN - 1) / BN);
-  // First tile that needs the causal mask for sub-block sb of this wavefront (retrieval heads).
+  // First tile that needs the causal mask for sub-block sb of this wavefront (causal lists).
   int t_mask[NSB];
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb) {
-    const int64_t x = a.pos0 + row_w + 32 * sb - BN + 1;
+    const int64_t x = a.pos0 + row_w + 32 * sb - gap - BN + 1;
     const int64_t tm = x < 0 ? 0 : x / BN + 1;
     t_mask[sb] = tm < t_whole_end ? (int)tm : t_whole_end;
   }
@@ -442,7 +447,7 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       // Mask (only tiles that touch the mask boundary or the end of the list).
-      const bool need_mask = !ks.retrieval || t >= t_mask[sb];
+      const bool need_mask = !causal_list || t >= t_mask[sb];
       // Online softmax for this lane's query column; `score(kb, r)` yields the masked score.
       auto softmax_block = [&](auto&& score) {
         float mx = -INFINITY;
@@ -490,8 +495,9 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
           for (int r = 0; r < 16; ++r) sv[kb][r] = s_acc[sb][kb][r];
         const int lim = clamp_i32(ks.total - ub);
         const int qa = clamp_i32(qpos[sb] - ub);             // query position relative to the tile
-        if (ks.retrieval) {
-          const int bound = qa < lim - 1 ? qa : lim - 1;     // visible iff u_rel <= bound
+        if (causal_list) {
+          const int qu = clamp_i32(qpos[sb] - gap - ub);     // the query's own list entry, relative to the tile
+          const int bound = qu < lim - 1 ? qu : lim - 1;     // visible iff u_rel <= bound
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
 #pragma unroll

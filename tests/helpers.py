@@ -61,7 +61,7 @@ def oracle_kv(k_bits, v_bits, fp8):
 
 
 def run_scenario(duo, cfg, q_bits, k_bits, v_bits, chunks, n_decode, fused_decode=False, want_lse=True,
-                 pass_params=False):
+                 pass_params=False, deployed=False):
     """Drive the library: prefill+append per chunk, then n_decode decode steps.
 
     cfg: dict(batch, hq, hkv, d, sink, recent, mask [hkv], max_seq, kv_dtype, scale)
@@ -82,7 +82,8 @@ def run_scenario(duo, cfg, q_bits, k_bits, v_bits, chunks, n_decode, fused_decod
         qd, kd, vd = (to_dev(x[:, pos:pos + n]) for x in (q_bits, k_bits, v_bits))
         od = torch.empty((b, n, hq, d), dtype=torch.bfloat16, device="cuda")
         ld = torch.empty((b, hq, n), dtype=torch.float32, device="cuda") if want_lse else None
-        duo.duo_attn_prefill(handle, 0, qd, kd, vd, n, od, lse=ld, params=params)
+        (duo.duo_attn_prefill_deployed if deployed else duo.duo_attn_prefill)(handle, 0, qd, kd, vd, n, od, lse=ld,
+                                                                              params=params)
         duo.duo_kv_append(handle, 0, kd, vd, n, params=params)
         torch.cuda.synchronize()
         out[:, pos:pos + n] = from_dev_bits(od)
@@ -111,12 +112,14 @@ def run_scenario(duo, cfg, q_bits, k_bits, v_bits, chunks, n_decode, fused_decod
     return out, lse, handle
 
 
-def oracle_rows(cfg, q_bits, k_bits, v_bits, positions, batch_idx=0):
-    """Oracle output/lse of the given positions of one sequence: (o [n,Hq,D], lse [Hq,n])."""
+def oracle_rows(cfg, q_bits, k_bits, v_bits, positions, batch_idx=0, chunk_starts=None):
+    """Oracle output/lse of the given positions of one sequence: (o [n,Hq,D], lse [Hq,n]).
+    chunk_starts (one per position) selects the deployed chunk-causal streaming attention."""
     kf, vf = oracle_kv(k_bits[batch_idx], v_bits[batch_idx], cfg.get("kv_dtype", 0) == 1)
     qf = synth.bf16_bits_to_f64(q_bits[batch_idx][np.asarray(positions)])
     scale = cfg.get("scale", 0.0) or None
-    return oracle.attention_rows(qf, kf, vf, positions, cfg["mask"], cfg["sink"], cfg["recent"], scale)
+    return oracle.attention_rows(qf, kf, vf, positions, cfg["mask"], cfg["sink"], cfg["recent"], scale,
+                                 chunk_starts=chunk_starts)
 
 
 # ---- full-size cases: inputs generated on the device, the CPU regenerates the slices it checks

@@ -295,3 +295,29 @@ def test_decode_workgroups_that_cross_segment_borders():
 def test_all_streaming_and_all_retrieval_layers_on_the_matrix_core_kernel():
     for mask in (np.zeros(2, dtype=np.uint8), np.ones(2, dtype=np.uint8)):
         _decode_vs_oracle(8, 2, 128, 4, 16, 2, 150, 3, 0, mask)
+
+
+@pytest.mark.parametrize("hq,hkv,d,sink,recent,chunks,batch", [
+    (8, 8, 64, 16, 256, [700, 300, 1, 47, 1000], 1),      # configuration-1 constants, ragged chunks
+    (8, 2, 128, 4, 32, [300, 1, 77, 130, 64], 2),         # GQA 4, window shorter than a tile
+    (4, 4, 128, 64, 256, [129, 513, 200], 1),             # deployment constants
+    (4, 2, 64, 0, 5, [70, 70, 3], 1),                     # no sinks
+    (2, 2, 128, 1, 2, [4, 4, 4, 4], 1),                   # the figure's parameters
+])
+def test_deployed_chunk_causal_prefill(hq, hkv, d, sink, recent, chunks, batch):
+    # duo_attn_prefill_deployed: streaming heads see [retained cache || chunk] causally; the result
+    # depends on the chunk starts, which the oracle is given per position
+    total = sum(chunks)
+    mask = np.array([(h % 2) for h in range(hkv)], dtype=np.uint8)
+    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=sink, recent=recent, mask=mask, max_seq=total + 4)
+    q, k, v = make_qkv(hq * 10 + d + recent, batch, total + 4, hq, hkv, d)
+    out, lse, handle = run_scenario(duo, cfg, q, k, v, chunks, 4, deployed=True)
+    duo.duo_cache_destroy(handle)
+    starts = np.concatenate([np.full(n, p) for p, n in zip(np.cumsum([0] + chunks[:-1]), chunks)])
+    for b in range(batch):
+        want_o, want_lse = oracle_rows(cfg, q, k, v, np.arange(total), b, chunk_starts=starts)
+        assert_close(synth.bf16_bits_to_f64(out[b][:total]), want_o, "deployed prefill, batch %d" % b)
+        assert np.abs(lse[b][:, :total] - want_lse).max() <= ATOL_LSE
+        # the decode steps after it see the ordinary cache contents
+        want_d, _ = oracle_rows(cfg, q, k, v, np.arange(total, total + 4), b)
+        assert_close(synth.bf16_bits_to_f64(out[b][total:]), want_d, "decode after deployed prefill")
