@@ -28,3 +28,9 @@ from .fp8_codec import (  # noqa: F401
     quantize_rows,
     dequantize_rows,
 )
+from .int4_codec import (  # noqa: F401
+    quantize_rows_int4,
+    dequantize_rows_int4,
+    pack_int4,
+    unpack_int4,
+)
