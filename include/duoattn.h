@@ -52,11 +52,16 @@ typedef enum {
 
 typedef enum {
   DUO_KV_BF16 = 0,    /* caches hold the bf16 rows unchanged */
-  DUO_KV_FP8_E4M3 = 1 /* caches hold OCP E4M3 codes + one fp32 scale per (token, KV head),
+  DUO_KV_FP8_E4M3 = 1,/* caches hold OCP E4M3 codes + one fp32 scale per (token, KV head),
                          K and V separately: scale = amax/448 (1 if the row is all zero),
                          code = RNE-saturating(x / scale), x_hat = value(code) * scale.
                          This stands in for the paper's 4-bit KV setting (Section 3.4,
                          combination with quantization). */
+  DUO_KV_INT4 = 2     /* caches hold 4-bit codes, two per byte (element 2i in the low nibble), + two fp32
+                         per (token, KV head), K and V separately: (scale, lo) with lo = min x,
+                         scale = (max x - lo) / 15 (1 for a constant row), code = clamp(round-to-nearest-
+                         even((x - lo) / scale), 0, 15) in fp32, x_hat = code * scale + lo.  The paper's own
+                         capacity setting is a 4-bit KV cache (Section 3.4) whose codec it does not give. */
 } duo_kv_dtype_t;
 
 typedef struct {
@@ -147,8 +152,8 @@ int duo_decode_step(duo_cache_t* cache, int layer, const void* q, const void* k,
 /* Test hook: the tokens one (layer, sequence, KV head) cache currently holds, in
  * ascending position order.  k_out/v_out: device buffers of capacity
  * `capacity` rows, each row head_dim bf16 (DUO_KV_BF16) or head_dim bytes
- * (DUO_KV_FP8_E4M3); kscale_out/vscale_out: fp32 [capacity], fp8 mode only (may
- * be NULL otherwise); positions_out: device int64 [capacity].  *count_out (HOST)
+ * (DUO_KV_FP8_E4M3) or head_dim / 2 bytes (DUO_KV_INT4); kscale_out/vscale_out: fp32 [capacity]
+ * (fp8) or fp32 [capacity][2] = (scale, lo) pairs (int4), NULL allowed for bf16; positions_out: device int64 [capacity].  *count_out (HOST)
  * receives the number of rows.  DUO_ERANGE if capacity is too small. */
 int duo_cache_export(duo_cache_t* cache, int layer, int batch_idx, int kv_head,
                      void* k_out, void* v_out, float* kscale_out, float* vscale_out,

@@ -95,7 +95,7 @@ int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
   const int64_t kMinKeysPerSplit = 256;
   const int64_t heads = (int64_t)L.view.n_ret * c->cfg.batch;
   if (heads == 0) return 1;
-  const int64_t slots = (L.view.group >= 2 || c->cfg.kv_dtype == DUO_KV_FP8_E4M3) ? 512 : 256;
+  const int64_t slots = (L.view.group >= 2 || c->cfg.kv_dtype != DUO_KV_BF16) ? 512 : 256;
   int64_t budget = slots - (int64_t)L.view.n_str * c->cfg.batch;
   if (budget < slots / 2) budget = slots / 2;
   int64_t s = budget / heads;
@@ -159,7 +159,7 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   if (cfg->max_seq < 1) return fail(DUO_EINVAL, "max_seq must be >= 1 (got %lld)", (long long)cfg->max_seq);
   if (cfg->max_seq > ((int64_t)1 << 31) - 1024)
     return fail(DUO_EINVAL, "max_seq %lld exceeds the supported 2^31 - 1024", (long long)cfg->max_seq);
-  if (cfg->kv_dtype != DUO_KV_BF16 && cfg->kv_dtype != DUO_KV_FP8_E4M3)
+  if (cfg->kv_dtype != DUO_KV_BF16 && cfg->kv_dtype != DUO_KV_FP8_E4M3 && cfg->kv_dtype != DUO_KV_INT4)
     return fail(DUO_EINVAL, "kv_dtype %d unknown", cfg->kv_dtype);
   if (!cfg->retrieval_mask) return fail(DUO_EINVAL, "retrieval_mask must not be NULL");
   if (!(cfg->softmax_scale >= 0.0f) || std::isinf(cfg->softmax_scale))
@@ -171,8 +171,10 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   c->cfg.retrieval_mask = nullptr;
   c->layers.resize(cfg->n_layers);
 
-  const bool fp8 = cfg->kv_dtype == DUO_KV_FP8_E4M3;
-  const int row_bytes = fp8 ? cfg->head_dim : cfg->head_dim * 2;
+  const int sc_per_row = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? 1 : (cfg->kv_dtype == DUO_KV_INT4 ? 2 : 0);
+  const bool fp8 = sc_per_row > 0;   // any quantised mode: scale arrays are allocated
+  const int row_bytes = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? cfg->head_dim
+                        : (cfg->kv_dtype == DUO_KV_INT4 ? cfg->head_dim / 2 : cfg->head_dim * 2);
   const int64_t str_rows = (int64_t)cfg->sink + cfg->recent;
   const float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   const int hkv = cfg->n_kv_heads, hq = cfg->n_q_heads;
@@ -209,12 +211,12 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
     v.n_ret = n_ret; v.n_str = n_str;
     v.batch = cfg->batch; v.n_q_heads = hq; v.n_kv_heads = hkv; v.group = group;
     v.head_dim = cfg->head_dim; v.sink = cfg->sink; v.recent = cfg->recent;
-    v.row_bytes = row_bytes; v.fp8 = fp8 ? 1 : 0; v.max_seq = cfg->max_seq; v.scale = scale;
+    v.row_bytes = row_bytes; v.kv_mode = cfg->kv_dtype; v.sc_per_row = sc_per_row; v.max_seq = cfg->max_seq; v.scale = scale;
 
     const size_t ret_bytes = (size_t)cfg->batch * n_ret * (size_t)cfg->max_seq * row_bytes;
     const size_t str_bytes = (size_t)cfg->batch * n_str * (size_t)str_rows * row_bytes;
-    const size_t ret_sc = (size_t)cfg->batch * n_ret * (size_t)cfg->max_seq * sizeof(float);
-    const size_t str_sc = (size_t)cfg->batch * n_str * (size_t)str_rows * sizeof(float);
+    const size_t ret_sc = (size_t)cfg->batch * n_ret * (size_t)cfg->max_seq * sizeof(float) * sc_per_row;
+    const size_t str_sc = (size_t)cfg->batch * n_str * (size_t)str_rows * sizeof(float) * sc_per_row;
     struct { void** p; size_t bytes; bool needed; } want[] = {
         {(void**)&v.k_ret, ret_bytes, n_ret > 0}, {(void**)&v.v_ret, ret_bytes, n_ret > 0},
         {(void**)&v.k_str, str_bytes, n_str > 0}, {(void**)&v.v_str, str_bytes, n_str > 0},
@@ -357,7 +359,7 @@ static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k
   hipError_t e;
   // one query head per KV head on a bf16 cache: the vector-unit kernel; query groups and fp8
   // caches: the matrix-core kernel
-  const bool use_sk = c->force_matrix_decode || L.view.group >= 2 || c->cfg.kv_dtype == DUO_KV_FP8_E4M3;
+  const bool use_sk = c->force_matrix_decode || L.view.group >= 2 || c->cfg.kv_dtype != DUO_KV_BF16;
   if (use_sk) {
     const int64_t unit = duo::kDecodeUnitRows;
     const int64_t rows_str = duo::streaming_rows(L.len, c->cfg.sink, c->cfg.recent);
@@ -391,8 +393,8 @@ int duo_cache_export(duo_cache_t* c, int layer, int batch_idx, int kv_head, void
   if (batch_idx < 0 || batch_idx >= c->cfg.batch) return fail(DUO_ERANGE, "batch_idx %d outside [0, %d)", batch_idx, c->cfg.batch);
   if (kv_head < 0 || kv_head >= c->cfg.n_kv_heads) return fail(DUO_ERANGE, "kv_head %d outside [0, %d)", kv_head, c->cfg.n_kv_heads);
   if (!k_out || !v_out || !positions_out || !count_out) return fail(DUO_EINVAL, "k_out, v_out, positions_out and count_out must not be NULL");
-  const bool fp8 = c->cfg.kv_dtype == DUO_KV_FP8_E4M3;
-  if (fp8 && (!kscale_out || !vscale_out)) return fail(DUO_EINVAL, "scale outputs are required for an fp8 cache");
+  const bool fp8 = c->cfg.kv_dtype != DUO_KV_BF16;
+  if (fp8 && (!kscale_out || !vscale_out)) return fail(DUO_EINVAL, "scale outputs are required for a quantised cache");
   Layer& L = c->layers[layer];
   int64_t count = L.mask[kv_head] ? L.len : duo::streaming_rows(L.len, c->cfg.sink, c->cfg.recent);
   if (count > capacity) return fail(DUO_ERANGE, "export needs %lld rows but capacity is %lld", (long long)count, (long long)capacity);

@@ -35,7 +35,8 @@ __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0
 
 // One 16-byte chunk (8 bf16 values) of one row per thread; the head_dim/8 threads
 // of a row sit in adjacent lanes.
-template <int D, bool FP8>
+// MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 codes + (scale, minimum).
+template <int D, int MODE>
 __global__ __launch_bounds__(256) void append_kernel(LayerView lv, const uint4* __restrict__ k_in,
                                                      const uint4* __restrict__ v_in, int64_t pos0,
                                                      int n_new, int64_t total_rows) {
@@ -72,12 +73,56 @@ __global__ __launch_bounds__(256) void append_kernel(LayerView lv, const uint4* 
   }
   const uint4 kc = k_in[r * LPR + sub];
   const uint4 vc = v_in[r * LPR + sub];
-  if constexpr (!FP8) {
+  if constexpr (MODE == 0) {
     if (write) {
       uint4* kd = (uint4*)(retrieval ? lv.k_ret : lv.k_str);
       uint4* vd = (uint4*)(retrieval ? lv.v_ret : lv.v_str);
       kd[dst_row * LPR + sub] = kc;
       vd[dst_row * LPR + sub] = vc;
+    }
+  } else if constexpr (MODE == 2) {
+    // asymmetric 4-bit codes per row, all in fp32: lo = min, scale = (max - lo) / 15 (1 for a
+    // constant row), code = clamp(rint((x - lo) / scale), 0, 15); element j of the lane's eight
+    // goes to bits 4 j of its dword, so element 2 i sits in the low nibble of byte i of the row
+    const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
+    const uint32_t vw[4] = {vc.x, vc.y, vc.z, vc.w};
+    float kf[8], vf[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      kf[2 * i] = bf16_lo(kw[i]); kf[2 * i + 1] = bf16_hi(kw[i]);
+      vf[2 * i] = bf16_lo(vw[i]); vf[2 * i + 1] = bf16_hi(vw[i]);
+    }
+    float kmin = kf[0], kmax = kf[0], vmin = vf[0], vmax = vf[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+      kmin = fminf(kmin, kf[i]); kmax = fmaxf(kmax, kf[i]);
+      vmin = fminf(vmin, vf[i]); vmax = fmaxf(vmax, vf[i]);
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) {
+      kmin = fminf(kmin, __shfl_xor(kmin, off)); kmax = fmaxf(kmax, __shfl_xor(kmax, off));
+      vmin = fminf(vmin, __shfl_xor(vmin, off)); vmax = fmaxf(vmax, __shfl_xor(vmax, off));
+    }
+    const float kspan = kmax - kmin, vspan = vmax - vmin;
+    const float ks = kspan == 0.f ? 1.0f : kspan / 15.0f;
+    const float vs = vspan == 0.f ? 1.0f : vspan / 15.0f;
+    uint32_t kq = 0, vq = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float kr = fminf(fmaxf(rintf((kf[i] - kmin) / ks), 0.f), 15.f);
+      const float vr = fminf(fmaxf(rintf((vf[i] - vmin) / vs), 0.f), 15.f);
+      kq |= (uint32_t)kr << (4 * i);
+      vq |= (uint32_t)vr << (4 * i);
+    }
+    if (write) {
+      uint32_t* kd = (uint32_t*)(retrieval ? lv.k_ret : lv.k_str);
+      uint32_t* vd = (uint32_t*)(retrieval ? lv.v_ret : lv.v_str);
+      kd[dst_row * LPR + sub] = kq;
+      vd[dst_row * LPR + sub] = vq;
+      if (sub == 0) {
+        ((float2*)(retrieval ? lv.ks_ret : lv.ks_str))[dst_row] = make_float2(ks, kmin);
+        ((float2*)(retrieval ? lv.vs_ret : lv.vs_str))[dst_row] = make_float2(vs, vmin);
+      }
     }
   } else {
     const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
@@ -151,9 +196,11 @@ __global__ __launch_bounds__(256) void export_kernel(LayerView lv, int batch_idx
   ((uint32_t*)v_out)[idx * words_per_row + w] = vs[src_row * words_per_row + w];
   if (w == 0) {
     pos_out[idx] = p;
-    if (lv.fp8) {
-      ks_out[idx] = (retrieval ? lv.ks_ret : lv.ks_str)[src_row];
-      vs_out[idx] = (retrieval ? lv.vs_ret : lv.vs_str)[src_row];
+    const float* ksrc = retrieval ? lv.ks_ret : lv.ks_str;
+    const float* vsrc = retrieval ? lv.vs_ret : lv.vs_str;
+    for (int j = 0; j < lv.sc_per_row; ++j) {
+      ks_out[idx * lv.sc_per_row + j] = ksrc[src_row * lv.sc_per_row + j];
+      vs_out[idx * lv.sc_per_row + j] = vsrc[src_row * lv.sc_per_row + j];
     }
   }
 }
@@ -169,13 +216,18 @@ hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int6
   dim3 grid((unsigned)blocks), block(256);
   const uint4* kk = (const uint4*)k;
   const uint4* vv = (const uint4*)v;
+#define DUO_APPEND(D_, M_) append_kernel<D_, M_><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows)
+  if (lv.kv_mode < 0 || lv.kv_mode > 2) return hipErrorInvalidValue;
   if (lv.head_dim == 128) {
-    if (lv.fp8) append_kernel<128, true><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
-    else append_kernel<128, false><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
+    if (lv.kv_mode == 2) DUO_APPEND(128, 2);
+    else if (lv.kv_mode == 1) DUO_APPEND(128, 1);
+    else DUO_APPEND(128, 0);
   } else {
-    if (lv.fp8) append_kernel<64, true><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
-    else append_kernel<64, false><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows);
+    if (lv.kv_mode == 2) DUO_APPEND(64, 2);
+    else if (lv.kv_mode == 1) DUO_APPEND(64, 1);
+    else DUO_APPEND(64, 0);
   }
+#undef DUO_APPEND
   return hipGetLastError();
 }
 

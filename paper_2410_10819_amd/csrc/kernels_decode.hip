@@ -527,7 +527,7 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
   const LayerView& lv = a.lv;
   // this kernel serves one query head per KV head on a bf16 cache; everything else goes to the
   // matrix-core kernel
-  if (lv.group != 1 || lv.fp8) return hipErrorInvalidValue;
+  if (lv.group != 1 || lv.kv_mode != 0) return hipErrorInvalidValue;
   if (a.splits < 1 || a.splits > kMaxDecodeSplits) return hipErrorInvalidValue;
   dim3 grid(lv.n_ret * a.splits + lv.n_str, lv.batch);
   if (lv.head_dim == 128) decode_kernel<128, 1, false><<<grid, 256, 0, stream>>>(a);

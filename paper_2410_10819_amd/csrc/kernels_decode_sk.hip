@@ -27,6 +27,15 @@
 //     barrier in the main loop.
 //   - fp8 caches: codes are widened to bf16 on the way (exact), the K scale
 //     multiplies the score and the V scale the probability of its key.
+//   - int4 caches (value = code * scale + lo per row): a code c becomes the bf16
+//     value 128 + c by OR-ing its nibble into 0x4300, two codes per instruction.
+//     With A = sum_d q_d (128 + c_d) from the matrix core and qsum = sum_d q_d the
+//     score is scale * A + (lo - 128 scale) * qsum; with p' = bf16(p * scale_v)
+//     the output is sum_key p' (128 + c) (matrix core) + sum_key (p (lo_v + 7.5 scale_v)
+//     - 135.5 p'), the second sum one scalar per head; taking the codes' midpoint
+//     out with p' as rounded leaves the rounding of p' acting on c - 7.5 only.  The nibble extraction leaves the eight
+//     values of a dword in the order 0 4 1 5 2 6 3 7; the query operand and the
+//     output index are permuted to match, so no instruction is spent on order.
 #include "duo_internal.h"
 
 namespace duo {
@@ -86,32 +95,55 @@ __device__ inline uint2 e4m3x4_to_bf16x4(uint32_t w) {
   return r;
 }
 
-template <int D, bool FP8>
+// Eight 4-bit codes (one dword, code j at bits 4 j) -> eight bf16 values 128 + code as four
+// dwords holding the code pairs (0,4) (1,5) (2,6) (3,7).
+__device__ inline uint4 int4x8_to_bf16x8(uint32_t w) {
+  constexpr uint32_t kMask = 0x000F000Fu, kBias = 0x43004300u;   // bf16 0x4300 = 128, one ulp = 1
+  uint4 r;
+  r.x = (w & kMask) | kBias;
+  r.y = ((w >> 4) & kMask) | kBias;
+  r.z = ((w >> 8) & kMask) | kBias;
+  r.w = ((w >> 12) & kMask) | kBias;
+  return r;
+}
+// position e of such a group of eight holds element sigma(e)
+__device__ inline int int4_sigma(int e) { return (e >> 1) + 4 * (e & 1); }
+
+// MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 codes + (scale, lo).
+template <int D, int MODE>
 struct Shape {
   static constexpr int NKK = D / 32;                 // matrix-core k-steps of K Q^T
   static constexpr int NMB = D / 16;                 // 16-row blocks of O^T
   static constexpr int LROW = D * 2;                 // bytes of a (bf16) V row in LDS
   static constexpr int CPR = D / 8;                  // 16-byte pieces per LDS row
-  static constexpr int GROW = FP8 ? D : D * 2;       // bytes of a row in the cache
+  static constexpr int GROW = MODE == 2 ? D / 2 : (MODE == 1 ? D : D * 2);   // bytes of a row in the cache
   static constexpr int VPR = GROW / 16;              // 16-byte pieces per cache row
   static constexpr int VRPI = 64 / VPR;              // V rows covered by one wavefront load
   static constexpr int NV = kUnit / VRPI;            // V loads per lane and block
-  static constexpr int KB = FP8 ? 8 : 16;            // bytes of K per lane, 16-key group and k-step
+  static constexpr int KB = MODE == 2 ? 4 : (MODE == 1 ? 8 : 16);   // bytes of K per lane, 16-key group and k-step
+  static constexpr int NSC = MODE == 2 ? 2 : 1;      // floats per row in the scale arrays
   __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
 };
 
 // Raw registers of one 32-row block as loaded from the cache.
-template <int D, bool FP8>
+template <int D, int MODE>
 struct RawBlock {
-  using S = Shape<D, FP8>;
+  using S = Shape<D, MODE>;
   uint32_t k[2][S::NKK][S::KB / 4];
   uint4 v[S::NV];
-  float sc;   // fp8: K scale of row `lane` (lanes 0..31) or V scale of row `lane - 32`
+  float sc[S::NSC];   // quantised: K parameters of row `lane` (lanes 0..31) or V parameters of row `lane - 32`
 };
 
-template <int D, bool FP8>
+// Per-key dequantisation parameters of a block in the lane's key order (keys 16 t + 4 qd + r at
+// index 4 t + r).  fp8: ks, vs.  int4: ks, koff = lo_k - 128 ks, vs, vlo = lo_v + 7.5 vs.
+struct KeyParams {
+  float ks[8], koff[8], vs[8], vlo[8];
+};
+
+template <int D, int MODE>
 __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
-  using S = Shape<D, FP8>;
+  using S = Shape<D, MODE>;
+  constexpr bool FP8 = MODE == 1, INT4 = MODE == 2, QUANT = MODE != 0;
   constexpr int NKK = S::NKK, NMB = S::NMB, LROW = S::LROW, GROW = S::GROW;
   const LayerView& lv = a.lv;
   const int G = lv.group;
@@ -122,7 +154,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
 
   // LDS: per-wavefront V staging; later reused for the merges.
   __shared__ __attribute__((aligned(16))) uint8_t sm_v[4][kUnit * LROW];
-  __shared__ __attribute__((aligned(16))) float sm_sc[4][64];
+  __shared__ __attribute__((aligned(16))) float sm_sc[4][64 * S::NSC];
   __shared__ __attribute__((aligned(16))) uint16_t sm_new[2][D];
   __shared__ float sm_m[4][16], sm_l[4][16], sm_m2[16], sm_l2[16];
   __shared__ int sm_last;
@@ -163,7 +195,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       const int64_t head_row0 = ((int64_t)b * lv.n_ret + slot) * lv.max_seq;
       kbase = lv.k_ret + head_row0 * GROW;
       vbase = lv.v_ret + head_row0 * GROW;
-      if (FP8) { ksbase = lv.ks_ret + head_row0; vsbase = lv.vs_ret + head_row0; }
+      if (QUANT) { ksbase = lv.ks_ret + head_row0 * S::NSC; vsbase = lv.vs_ret + head_row0 * S::NSC; }
     } else {
       const int64_t s2 = (u - ret_units_all) / a.units_str;
       seg = n_ret_seg + s2;
@@ -181,7 +213,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       const int64_t head_row0 = ((int64_t)b * lv.n_str + slot) * cap;
       kbase = lv.k_str + head_row0 * GROW;
       vbase = lv.v_str + head_row0 * GROW;
-      if (FP8) { ksbase = lv.ks_str + head_row0; vsbase = lv.vs_str + head_row0; }
+      if (QUANT) { ksbase = lv.ks_str + head_row0 * S::NSC; vsbase = lv.vs_str + head_row0 * S::NSC; }
     }
     const int64_t seg_e = seg_a + seg_units;
     const int64_t part_e = u_hi < seg_e ? u_hi : seg_e;
@@ -192,15 +224,29 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     const bool with_new = a.k_new != nullptr && part_e == seg_e;   // the part that ends the segment owns the new token
     const int64_t last_row = n_rows > 0 ? n_rows - 1 : 0;
 
-    // ---- query operand: lane (hd, qd) holds q[head hd][32 kk + 8 qd .. + 7]
+    // ---- query operand: lane (hd, qd) holds q[head hd][32 kk + 8 qd .. + 7]; for an int4 cache,
+    // whose lanes load D/4 consecutive codes of a key, q[head hd][(D/4) qd + 8 kk + sigma(0..7)]
     bf16x8 qf[NKK];
+    float qsum_c = 0.f;   // int4: c_scale * sum_d q[head hd][d]
     {
       const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G + (head_ok ? hd : 0)) * D;
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
-        uint4 raw = *(const uint4*)(qrow + 32 * kk + 8 * qd);
+        uint4 raw = *(const uint4*)(qrow + (INT4 ? (D / 4) * qd + 8 * kk : 32 * kk + 8 * qd));
         if (!head_ok) raw = make_uint4(0, 0, 0, 0);
+        if constexpr (INT4) {
+          const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) qsum_c += __uint_as_float(w[i] << 16) + __uint_as_float(w[i] & 0xFFFF0000u);
+          raw = make_uint4(__builtin_amdgcn_perm(raw.z, raw.x, 0x05040100u), __builtin_amdgcn_perm(raw.z, raw.x, 0x07060302u),
+                           __builtin_amdgcn_perm(raw.w, raw.y, 0x05040100u), __builtin_amdgcn_perm(raw.w, raw.y, 0x07060302u));
+        }
         qf[kk] = __builtin_bit_cast(bf16x8, raw);
+      }
+      if constexpr (INT4) {
+        qsum_c += __shfl_xor(qsum_c, 16);
+        qsum_c += __shfl_xor(qsum_c, 32);
+        qsum_c *= c_scale;
       }
     }
 
@@ -209,19 +255,33 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
 #pragma unroll
     for (int mb = 0; mb < NMB; ++mb) oacc[mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m_ref = -INFINITY, l_lane = 0.f;
+    float corr_lane = 0.f;   // int4: sum over the lane's keys of p (lo_v + 7.5 scale_v) - 135.5 bf16(p scale_v)
 
-    using Raw = RawBlock<D, FP8>;
+    using Raw = RawBlock<D, MODE>;
     // Loads of a block whose 32 rows are all present: a uniform block address plus per-lane
     // offsets that never change (K: row hd of each 16-key group, piece qd + 4 kk; V: the block's
     // rows are one contiguous run, 16 bytes per lane and load).
-    const uint32_t k_off = (uint32_t)(hd * GROW + qd * S::KB);
+    const uint32_t k_off = (uint32_t)(hd * GROW + qd * (INT4 ? D / 8 : S::KB));
     const uint32_t v_off = (uint32_t)(lane * 16);
+    // int4: the D/8 bytes of one key that belong to this lane, all k-steps in one load
+    auto load_k_int4 = [&](Raw& rb, int t, const uint8_t* p) {
+      if constexpr (D == 128) {
+        const uint4 x = *(const uint4*)p;
+        rb.k[t][0][0] = x.x; rb.k[t][1][0] = x.y; rb.k[t][2][0] = x.z; rb.k[t][3][0] = x.w;
+      } else {
+        const uint2 x = *(const uint2*)p;
+        rb.k[t][0][0] = x.x; rb.k[t][1][0] = x.y;
+      }
+    };
     auto issue = [&](Raw& rb, int blk) {
       const int64_t r0 = row0 + (int64_t)blk * kUnit;
       const uint8_t* kb = kbase + r0 * GROW;
       const uint8_t* vb = vbase + r0 * GROW;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
+        if constexpr (INT4) {
+          load_k_int4(rb, t, kb + (k_off + (uint32_t)(16 * t * GROW)));
+        } else {
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           const uint8_t* p = kb + (k_off + (uint32_t)(16 * t * GROW + 4 * kk * S::KB));
@@ -233,9 +293,14 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
             rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y; rb.k[t][kk][2] = x.z; rb.k[t][kk][3] = x.w;
           }
         }
+        }
 #pragma unroll
       for (int j = 0; j < S::NV; ++j) rb.v[j] = *(const uint4*)(vb + (v_off + (uint32_t)(j * 1024)));
-      if constexpr (FP8) rb.sc = (lane < 32 ? ksbase : vsbase)[r0 + (lane & 31)];
+      if constexpr (FP8) rb.sc[0] = (lane < 32 ? ksbase : vsbase)[r0 + (lane & 31)];
+      if constexpr (INT4) {
+        const float2 x = ((const float2*)(lane < 32 ? ksbase : vsbase))[r0 + (lane & 31)];
+        rb.sc[0] = x.x; rb.sc[1] = x.y;
+      }
     };
     // The same for the last, partly filled block of a segment: rows past the end are redirected
     // to the last row present (and masked later).
@@ -246,9 +311,11 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         int64_t r = r0 + 16 * t + hd;
         r = r < n_rows ? r : last_row;
         const uint8_t* kr = kbase + r * GROW;
+        if constexpr (INT4) load_k_int4(rb, t, kr + qd * (D / 8));
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
-          if constexpr (FP8) {
+          if constexpr (INT4) {
+          } else if constexpr (FP8) {
             const uint2 x = *(const uint2*)(kr + (qd + 4 * kk) * 8);
             rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y;
           } else {
@@ -263,10 +330,15 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         r = r < n_rows ? r : last_row;
         rb.v[j] = *(const uint4*)(vbase + r * GROW + (lane % S::VPR) * 16);
       }
-      if constexpr (FP8) {
+      if constexpr (QUANT) {
         int64_t r = r0 + (lane & 31);
         r = r < n_rows ? r : last_row;
-        rb.sc = (lane < 32 ? ksbase : vsbase)[r];
+        if constexpr (INT4) {
+          const float2 x = ((const float2*)(lane < 32 ? ksbase : vsbase))[r];
+          rb.sc[0] = x.x; rb.sc[1] = x.y;
+        } else {
+          rb.sc[0] = (lane < 32 ? ksbase : vsbase)[r];
+        }
       }
     };
 
@@ -282,8 +354,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     };
     // Softmax update and O^T += V^T P^T of one block whose V rows are staged in my_v (bf16).
     // key_base: row index of the block's first key; keys >= valid_end are masked.
-    auto finish = [&](const f32x4 (&sacc)[2], const float (&ksc)[8], const float (&vsc)[8],
-                      int64_t key_base, int64_t valid_end) {
+    auto finish = [&](const f32x4 (&sacc)[2], const KeyParams& kp, int64_t key_base, int64_t valid_end) {
       float sv[8];
       float lmax = -INFINITY;
 #pragma unroll
@@ -291,8 +362,13 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int64_t key = key_base + 16 * t + 4 * qd + r;
-          float s = sacc[t][r] * c_scale;
-          if constexpr (FP8) s *= ksc[4 * t + r];
+          float s;
+          if constexpr (INT4) {
+            s = sacc[t][r] * (kp.ks[4 * t + r] * c_scale) + kp.koff[4 * t + r] * qsum_c;
+          } else {
+            s = sacc[t][r] * c_scale;
+            if constexpr (FP8) s *= kp.ks[4 * t + r];
+          }
           const bool ok = head_ok && key < valid_end && key != exclude;
           s = ok ? s : -INFINITY;
           sv[4 * t + r] = s;
@@ -305,6 +381,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         const float mu = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = fast_exp2(m_ref - mu);
         l_lane *= alpha;
+        if constexpr (INT4) corr_lane *= alpha;
 #pragma unroll
         for (int mb = 0; mb < NMB; ++mb) oacc[mb] *= alpha;
         m_ref = m_new;
@@ -317,7 +394,13 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       l_lane += psum;
       bf16x8 pb;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) pb[i] = (__bf16)(FP8 ? p[i] * vsc[i] : p[i]);
+      for (int i = 0; i < 8; ++i) pb[i] = (__bf16)(QUANT ? p[i] * kp.vs[i] : p[i]);
+      if constexpr (INT4) {
+        // the matrix core sums pb * (128 + code) = pb * (code - 7.5) + 135.5 pb: take the second
+        // term back exactly as rounded; kp.vlo holds lo + 7.5 scale
+#pragma unroll
+        for (int i = 0; i < 8; ++i) corr_lane += p[i] * kp.vlo[i] - 135.5f * (float)pb[i];
+      }
       // O^T += V^T P^T : lane (hd, qd) supplies the address of key 16 h + 4 qd + (hd >> 2), d 16 mb + 4 (hd & 3)
       const int e = hd >> 2, i4 = hd & 3;
 #pragma unroll
@@ -336,11 +419,16 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     // Convert / stage the raw registers of a block (V rows into the wavefront's LDS buffer, 16-byte
     // pieces swizzled by row; fp8 scales through LDS into key order) and start its arithmetic.
     // After this the raw registers are free for the next block's loads.
-    auto stage_qk = [&](const Raw& rb, f32x4 (&sacc)[2], float (&ksc)[8], float (&vsc)[8]) {
+    auto stage_qk = [&](const Raw& rb, f32x4 (&sacc)[2], KeyParams& kp) {
 #pragma unroll
       for (int j = 0; j < S::NV; ++j) {
         const int row = j * S::VRPI + lane / S::VPR, pc = lane % S::VPR;
-        if constexpr (FP8) {
+        if constexpr (INT4) {
+          const uint32_t w[4] = {rb.v[j].x, rb.v[j].y, rb.v[j].z, rb.v[j].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            *(uint4*)(my_v + row * LROW + (((4 * pc + i) ^ S::v_swz(row)) * 16)) = int4x8_to_bf16x8(w[i]);
+        } else if constexpr (FP8) {
           const uint2 a0 = e4m3x4_to_bf16x4(rb.v[j].x), a1 = e4m3x4_to_bf16x4(rb.v[j].y);
           const uint2 a2 = e4m3x4_to_bf16x4(rb.v[j].z), a3 = e4m3x4_to_bf16x4(rb.v[j].w);
           *(uint4*)(my_v + row * LROW + (((2 * pc) ^ S::v_swz(row)) * 16)) = make_uint4(a0.x, a0.y, a1.x, a1.y);
@@ -354,7 +442,9 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
-          if constexpr (FP8) {
+          if constexpr (INT4) {
+            kf[t][kk] = __builtin_bit_cast(bf16x8, int4x8_to_bf16x8(rb.k[t][kk][0]));
+          } else if constexpr (FP8) {
             const uint2 x0 = e4m3x4_to_bf16x4(rb.k[t][kk][0]), x1 = e4m3x4_to_bf16x4(rb.k[t][kk][1]);
             kf[t][kk] = __builtin_bit_cast(bf16x8, make_uint4(x0.x, x0.y, x1.x, x1.y));
           } else {
@@ -362,18 +452,33 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
           }
         }
       qk(kf, sacc);
-      if constexpr (FP8) {
-        sm_sc[wave][lane] = rb.sc;
+      if constexpr (INT4) {
+        // [0..31] K scale, [32..63] K lo, [64..95] V scale, [96..127] V lo, each in row order
+        const int at = lane < 32 ? lane : lane + 32;
+        sm_sc[wave][at] = rb.sc[0];
+        sm_sc[wave][at + 32] = rb.sc[1];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const float4 s4 = *(const float4*)&sm_sc[wave][16 * t + 4 * qd];
+          const float4 l4 = *(const float4*)&sm_sc[wave][32 + 16 * t + 4 * qd];
+          const float4 v4 = *(const float4*)&sm_sc[wave][64 + 16 * t + 4 * qd];
+          const float4 o4 = *(const float4*)&sm_sc[wave][96 + 16 * t + 4 * qd];
+          kp.ks[4 * t] = s4.x; kp.ks[4 * t + 1] = s4.y; kp.ks[4 * t + 2] = s4.z; kp.ks[4 * t + 3] = s4.w;
+          kp.koff[4 * t] = l4.x - 128.f * s4.x; kp.koff[4 * t + 1] = l4.y - 128.f * s4.y;
+          kp.koff[4 * t + 2] = l4.z - 128.f * s4.z; kp.koff[4 * t + 3] = l4.w - 128.f * s4.w;
+          kp.vs[4 * t] = v4.x; kp.vs[4 * t + 1] = v4.y; kp.vs[4 * t + 2] = v4.z; kp.vs[4 * t + 3] = v4.w;
+          kp.vlo[4 * t] = o4.x + 7.5f * v4.x; kp.vlo[4 * t + 1] = o4.y + 7.5f * v4.y;
+          kp.vlo[4 * t + 2] = o4.z + 7.5f * v4.z; kp.vlo[4 * t + 3] = o4.w + 7.5f * v4.w;
+        }
+      } else if constexpr (FP8) {
+        sm_sc[wave][lane] = rb.sc[0];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const float4 kq = *(const float4*)&sm_sc[wave][16 * t + 4 * qd];
           const float4 vq = *(const float4*)&sm_sc[wave][32 + 16 * t + 4 * qd];
-          ksc[4 * t] = kq.x; ksc[4 * t + 1] = kq.y; ksc[4 * t + 2] = kq.z; ksc[4 * t + 3] = kq.w;
-          vsc[4 * t] = vq.x; vsc[4 * t + 1] = vq.y; vsc[4 * t + 2] = vq.z; vsc[4 * t + 3] = vq.w;
+          kp.ks[4 * t] = kq.x; kp.ks[4 * t + 1] = kq.y; kp.ks[4 * t + 2] = kq.z; kp.ks[4 * t + 3] = kq.w;
+          kp.vs[4 * t] = vq.x; kp.vs[4 * t + 1] = vq.y; kp.vs[4 * t + 2] = vq.z; kp.vs[4 * t + 3] = vq.w;
         }
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { ksc[i] = 1.f; vsc[i] = 1.f; }
       }
     };
 
@@ -388,15 +493,15 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     {
       Raw r0, r1, r2;
       f32x4 sacc[2];
-      float ksc[8], vsc[8];
+      KeyParams kp;
       const int n_my = wave < n_full ? (n_full - wave + 3) / 4 : 0;   // blocks of this wavefront
       auto blk_of = [&](int i) { return wave + 4 * i; };
       auto step = [&](Raw& rb, int i, bool prefetch) {
-        stage_qk(rb, sacc, ksc, vsc);
+        stage_qk(rb, sacc, kp);
         __builtin_amdgcn_sched_barrier(0);
         if (prefetch) issue(rb, blk_of(i + 3));
         __builtin_amdgcn_sched_barrier(0);
-        finish(sacc, ksc, vsc, row0 + (int64_t)blk_of(i) * kUnit, n_rows);
+        finish(sacc, kp, row0 + (int64_t)blk_of(i) * kUnit, n_rows);
         __builtin_amdgcn_sched_barrier(0);
       };
       if (n_my > 0) issue(r0, blk_of(0));
@@ -418,8 +523,8 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       }
       if (n_full < nb && wave == (n_full & 3)) {
         issue_tail(r0, n_full);
-        stage_qk(r0, sacc, ksc, vsc);
-        finish(sacc, ksc, vsc, row0 + (int64_t)n_full * kUnit, n_rows);
+        stage_qk(r0, sacc, kp);
+        finish(sacc, kp, row0 + (int64_t)n_full * kUnit, n_rows);
       }
     }
 
@@ -432,8 +537,50 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       const uint16_t* vin = (const uint16_t*)a.v_new + ((int64_t)b * lv.n_kv_heads + kvh) * D;
       uint4 kc = make_uint4(0, 0, 0, 0), vc = kc;
       if (row_lane) { kc = *(const uint4*)(kin + 8 * lane); vc = *(const uint4*)(vin + 8 * lane); }
-      float ks1 = 1.f, vs1 = 1.f;
-      if constexpr (!FP8) {
+      float ks1 = 1.f, vs1 = 1.f, klo1 = 0.f, vlo1 = 0.f;
+      if constexpr (INT4) {
+        // quantise exactly as the append kernel does, then attend to the codes like a cached row
+        const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w}, vw[4] = {vc.x, vc.y, vc.z, vc.w};
+        float kf4[8], vf4[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          kf4[2 * i] = __uint_as_float(kw[i] << 16); kf4[2 * i + 1] = __uint_as_float(kw[i] & 0xFFFF0000u);
+          vf4[2 * i] = __uint_as_float(vw[i] << 16); vf4[2 * i + 1] = __uint_as_float(vw[i] & 0xFFFF0000u);
+        }
+        float kmin = kf4[0], kmax = kf4[0], vmin = vf4[0], vmax = vf4[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) {
+          kmin = fminf(kmin, kf4[i]); kmax = fmaxf(kmax, kf4[i]);
+          vmin = fminf(vmin, vf4[i]); vmax = fmaxf(vmax, vf4[i]);
+        }
+        // the D/8 lanes of the row form an aligned lane group, so the exchange below stays inside it
+#pragma unroll
+        for (int off = 1; off < D / 8; off <<= 1) {
+          kmin = fminf(kmin, __shfl_xor(kmin, off)); kmax = fmaxf(kmax, __shfl_xor(kmax, off));
+          vmin = fminf(vmin, __shfl_xor(vmin, off)); vmax = fmaxf(vmax, __shfl_xor(vmax, off));
+        }
+        const float kspan = kmax - kmin, vspan = vmax - vmin;
+        ks1 = kspan == 0.f ? 1.0f : kspan / 15.0f;
+        vs1 = vspan == 0.f ? 1.0f : vspan / 15.0f;
+        uint32_t kq = 0, vq = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          kq |= (uint32_t)fminf(fmaxf(rintf((kf4[i] - kmin) / ks1), 0.f), 15.f) << (4 * i);
+          vq |= (uint32_t)fminf(fmaxf(rintf((vf4[i] - vmin) / vs1), 0.f), 15.f) << (4 * i);
+        }
+        if (a.commit && row_lane) {
+          *(uint32_t*)(kbase + new_row * GROW + lane * 4) = kq;
+          *(uint32_t*)(vbase + new_row * GROW + lane * 4) = vq;
+          if (lane == 0) {
+            ((float2*)ksbase)[new_row] = make_float2(ks1, kmin);
+            ((float2*)vsbase)[new_row] = make_float2(vs1, vmin);
+          }
+        }
+        kc = int4x8_to_bf16x8(kq);
+        vc = int4x8_to_bf16x8(vq);
+        ks1 = __shfl(ks1, 0); vs1 = __shfl(vs1, 0);
+        klo1 = __shfl(kmin, 0); vlo1 = __shfl(vmin, 0);
+      } else if constexpr (!FP8) {
         if (a.commit && row_lane) {
           *(uint4*)(kbase + new_row * GROW + lane * 16) = kc;
           *(uint4*)(vbase + new_row * GROW + lane * 16) = vc;
@@ -479,7 +626,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       bf16x8 kf[2][NKK];
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
-        uint4 x = *(const uint4*)&sm_new[0][32 * kk + 8 * qd];
+        uint4 x = *(const uint4*)&sm_new[0][INT4 ? (D / 4) * qd + 8 * kk : 32 * kk + 8 * qd];
         if (hd != 0) x = make_uint4(0, 0, 0, 0);
         kf[0][kk] = __builtin_bit_cast(bf16x8, x);
         kf[1][kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
@@ -489,26 +636,35 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         const int row = j * (64 / S::CPR) + lane / S::CPR, pc = lane % S::CPR;
         *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
       }
-      float ksc[8], vsc[8];
+      KeyParams kp;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { ksc[i] = ks1; vsc[i] = vs1; }
+      for (int i = 0; i < 8; ++i) { kp.ks[i] = ks1; kp.vs[i] = vs1; kp.koff[i] = klo1 - 128.f * ks1; kp.vlo[i] = vlo1 + 7.5f * vs1; }
       const int64_t saved = exclude;
       exclude = -1;
       f32x4 sacc[2];
       qk(kf, sacc);
-      finish(sacc, ksc, vsc, 0, 1);   // keys 0 .. 31 of a virtual block, only key 0 valid
+      finish(sacc, kp, 0, 1);   // keys 0 .. 31 of a virtual block, only key 0 valid
       exclude = saved;
     }
 
     // ---- merge the four wavefronts through LDS
     float l_head = l_lane + __shfl_xor(l_lane, 16);
     l_head += __shfl_xor(l_head, 32);
+    float corr_head = 0.f;
+    if constexpr (INT4) {
+      corr_head = corr_lane + __shfl_xor(corr_lane, 16);
+      corr_head += __shfl_xor(corr_head, 32);
+    }
     __syncthreads();   // every wavefront is done with its V staging buffer
     if (head_ok) {
 #pragma unroll
       for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sm_o[(wave * 16 + hd) * D + 16 * mb + 4 * qd + r] = oacc[mb][r];
+        for (int r = 0; r < 4; ++r) {
+          int pos = 16 * mb + 4 * qd + r;
+          if constexpr (INT4) pos = (pos & ~7) + int4_sigma(pos & 7);   // staged rows hold the code order 0 4 1 5 2 6 3 7
+          sm_o[(wave * 16 + hd) * D + pos] = oacc[mb][r] + corr_head;
+        }
       if (qd == 0) { sm_m[wave][hd] = m_ref; sm_l[wave][hd] = l_head; }
     }
     __syncthreads();
@@ -628,12 +784,15 @@ hipError_t launch_decode_sk(const DecodeArgs& a, hipStream_t stream) {
       (ret_units > 0 && a.ret_workers < 1) || a.units_ret < 1 || a.units_str < 1)
     return hipErrorInvalidValue;
   dim3 grid((unsigned)(a.ret_workers + lv.batch * lv.n_str));
+  if (lv.kv_mode < 0 || lv.kv_mode > 2) return hipErrorInvalidValue;
   if (lv.head_dim == 128) {
-    if (lv.fp8) decode_sk_kernel<128, true><<<grid, 256, 0, stream>>>(a);
-    else decode_sk_kernel<128, false><<<grid, 256, 0, stream>>>(a);
+    if (lv.kv_mode == 2) decode_sk_kernel<128, 2><<<grid, 256, 0, stream>>>(a);
+    else if (lv.kv_mode == 1) decode_sk_kernel<128, 1><<<grid, 256, 0, stream>>>(a);
+    else decode_sk_kernel<128, 0><<<grid, 256, 0, stream>>>(a);
   } else {
-    if (lv.fp8) decode_sk_kernel<64, true><<<grid, 256, 0, stream>>>(a);
-    else decode_sk_kernel<64, false><<<grid, 256, 0, stream>>>(a);
+    if (lv.kv_mode == 2) decode_sk_kernel<64, 2><<<grid, 256, 0, stream>>>(a);
+    else if (lv.kv_mode == 1) decode_sk_kernel<64, 1><<<grid, 256, 0, stream>>>(a);
+    else decode_sk_kernel<64, 0><<<grid, 256, 0, stream>>>(a);
   }
   return hipGetLastError();
 }

@@ -49,14 +49,17 @@ def assert_close(got_f64, want_f64, what=""):
     return diff.max(), diff.mean()
 
 
-def oracle_kv(k_bits, v_bits, fp8):
-    """float64 K/V history the oracle attends over (after the fp8 codec if enabled)."""
+def oracle_kv(k_bits, v_bits, kv_dtype):
+    """float64 K/V history the oracle attends over (after the fp8 (1) or int4 (2) codec if enabled)."""
     k = synth.bf16_bits_to_f64(k_bits)
     v = synth.bf16_bits_to_f64(v_bits)
-    if fp8:
+    if kv_dtype == 1:
         kc, ks = oracle.quantize_rows(k.astype(np.float32))
         vc, vs = oracle.quantize_rows(v.astype(np.float32))
         k, v = oracle.dequantize_rows(kc, ks), oracle.dequantize_rows(vc, vs)
+    elif kv_dtype == 2:
+        k = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(k.astype(np.float32)))
+        v = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(v.astype(np.float32)))
     return k, v
 
 
@@ -115,7 +118,7 @@ def run_scenario(duo, cfg, q_bits, k_bits, v_bits, chunks, n_decode, fused_decod
 def oracle_rows(cfg, q_bits, k_bits, v_bits, positions, batch_idx=0, chunk_starts=None):
     """Oracle output/lse of the given positions of one sequence: (o [n,Hq,D], lse [Hq,n]).
     chunk_starts (one per position) selects the deployed chunk-causal streaming attention."""
-    kf, vf = oracle_kv(k_bits[batch_idx], v_bits[batch_idx], cfg.get("kv_dtype", 0) == 1)
+    kf, vf = oracle_kv(k_bits[batch_idx], v_bits[batch_idx], int(cfg.get("kv_dtype", 0)))
     qf = synth.bf16_bits_to_f64(q_bits[batch_idx][np.asarray(positions)])
     scale = cfg.get("scale", 0.0) or None
     return oracle.attention_rows(qf, kf, vf, positions, cfg["mask"], cfg["sink"], cfg["recent"], scale,
@@ -165,17 +168,22 @@ def cpu_history_bits(seed, layer, tensor, batch_idx, n_tokens, n_heads, d, heads
     return out
 
 
-def oracle_history_f64(bits, fp8, workers=8):
-    """float64 history the oracle attends over: the bf16 values, or their fp8 round trip through the
-    oracle's codec (applied block by block; each row is coded independently)."""
-    if not fp8:
+def oracle_history_f64(bits, kv_dtype, workers=8):
+    """float64 history the oracle attends over: the bf16 values, or their round trip through the
+    oracle's fp8 (1) or int4 (2) codec (applied block by block; each row is coded independently)."""
+    kv_dtype = int(kv_dtype)
+    if not kv_dtype:
         return synth.bf16_bits_to_f64(bits)
     out = np.empty(bits.shape, dtype=np.float64)
     step = 1 << 14
 
     def job(p0):
-        codes, scales = oracle.quantize_rows(synth.bf16_bits_to_f32(bits[p0:p0 + step]))
-        out[p0:p0 + step] = oracle.dequantize_rows(codes, scales)
+        x = synth.bf16_bits_to_f32(bits[p0:p0 + step])
+        if kv_dtype == 2:
+            out[p0:p0 + step] = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(x))
+        else:
+            codes, scales = oracle.quantize_rows(x)
+            out[p0:p0 + step] = oracle.dequantize_rows(codes, scales)
 
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(workers) as pool:

@@ -235,6 +235,44 @@ def test_fp8_cache_decode(hq, hkv, d):
         duo.duo_cache_destroy(handle)
 
 
+@pytest.mark.parametrize("hq,hkv,d,batch,n_fill", [(8, 2, 128, 2, 700), (32, 8, 128, 1, 4200), (8, 4, 64, 3, 1111)])
+def test_int4_cache_decode(hq, hkv, d, batch, n_fill):
+    # 4-bit cache: fill by append, decode with the fused step (which quantises the new token itself)
+    # and with append-then-attend; the oracle attends over its own codec's round trip of the history
+    mask = np.array([(h + 1) % 2 for h in range(hkv)], dtype=np.uint8)
+    _decode_vs_oracle(hq, hkv, d, 8, 40, batch, n_fill, 5, 2, mask)
+    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=8, recent=40, mask=mask, max_seq=n_fill + 3, kv_dtype=2)
+    q, k, v = make_qkv(77, batch, n_fill + 3, hq, hkv, d)
+    out, lse, handle = run_scenario_decode_only(cfg, q, k, v, n_fill, 3)
+    for b in range(batch):
+        want_o, want_lse = oracle_rows(cfg, q, k, v, np.arange(n_fill, n_fill + 3), b)
+        assert_close(out[b], want_o, "int4 batch %d" % b)
+        assert np.abs(lse[b] - want_lse).max() <= ATOL_LSE
+
+
+def run_scenario_decode_only(cfg, q, k, v, n_fill, n_decode):
+    """Append n_fill tokens, then n_decode times append one token and attend (two calls per step)."""
+    import torch
+    b, hq, hkv, d = cfg["batch"], cfg["hq"], cfg["hkv"], cfg["d"]
+    handle = duo.duo_cache_create(1, b, hq, hkv, d, cfg["sink"], cfg["recent"], cfg["max_seq"],
+                                  np.asarray(cfg["mask"], dtype=np.uint8)[None], cfg["kv_dtype"])
+    try:
+        duo.duo_kv_append(handle, 0, to_dev(k[:, :n_fill]), to_dev(v[:, :n_fill]), n_fill)
+        out = np.zeros((b, n_decode, hq, d))
+        lse = np.zeros((b, hq, n_decode))
+        for t in range(n_decode):
+            p = n_fill + t
+            duo.duo_kv_append(handle, 0, to_dev(k[:, p:p + 1]), to_dev(v[:, p:p + 1]), 1)
+            od = torch.empty((b, 1, hq, d), dtype=torch.bfloat16, device="cuda")
+            ld = torch.empty((b, hq), dtype=torch.float32, device="cuda")
+            duo.duo_attn_decode(handle, 0, to_dev(q[:, p:p + 1]), od, lse=ld)
+            out[:, t] = from_dev_f64(od)[:, 0]
+            lse[:, :, t] = ld.cpu().numpy()
+    finally:
+        duo.duo_cache_destroy(handle)
+    return out, lse, handle
+
+
 def _decode_vs_oracle(hq, hkv, d, sink, recent, batch, n_fill, n_decode, kv_dtype, mask, kernel=0, splits=0,
                       check_batches=None, seed=91):
     """Fill by append, then n_decode one-launch steps; every output row against the oracle."""
@@ -268,7 +306,7 @@ def _decode_vs_oracle(hq, hkv, d, sink, recent, batch, n_fill, n_decode, kv_dtyp
         assert np.abs(got_lse[b] - want_lse).max() <= ATOL_LSE
 
 
-@pytest.mark.parametrize("d,kv_dtype", [(64, 0), (128, 0), (128, 1)])
+@pytest.mark.parametrize("d,kv_dtype", [(64, 0), (128, 0), (128, 1), (64, 2), (128, 2)])
 def test_matrix_core_decode_kernel_with_one_query_head_per_kv_head(d, kv_dtype):
     # the matrix-core kernel forced onto an MHA layer (it pads the single head to 16 columns);
     # the context starts empty-ish, crosses the 32-row unit size and wraps the ring
@@ -278,7 +316,7 @@ def test_matrix_core_decode_kernel_with_one_query_head_per_kv_head(d, kv_dtype):
     _decode_vs_oracle(4, 4, d, 5, 40, 1, 1500, 4, kv_dtype, mask, kernel=1, splits=7)
 
 
-@pytest.mark.parametrize("kv_dtype", [0, 1])
+@pytest.mark.parametrize("kv_dtype", [0, 1, 2])
 def test_query_group_of_eight(kv_dtype):
     mask = np.array([0, 1], dtype=np.uint8)
     _decode_vs_oracle(16, 2, 128, 4, 28, 2, 333, 6, kv_dtype, mask)

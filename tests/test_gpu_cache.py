@@ -11,12 +11,13 @@ pytestmark = pytest.mark.gpu
 
 
 def _export(handle, layer, b, h, d, fp8, capacity):
+    """fp8: the cache's kv_dtype (0 bf16, 1 fp8: d code bytes + a scale, 2 int4: d/2 bytes + (scale, lo))."""
     import torch
     if fp8:
-        ko = torch.zeros((capacity, d), dtype=torch.uint8, device="cuda")
-        vo = torch.zeros((capacity, d), dtype=torch.uint8, device="cuda")
-        ks = torch.zeros(capacity, dtype=torch.float32, device="cuda")
-        vs = torch.zeros(capacity, dtype=torch.float32, device="cuda")
+        ko = torch.zeros((capacity, d // fp8), dtype=torch.uint8, device="cuda")
+        vo = torch.zeros((capacity, d // fp8), dtype=torch.uint8, device="cuda")
+        ks = torch.zeros((capacity, fp8) if fp8 == 2 else capacity, dtype=torch.float32, device="cuda")
+        vs = torch.zeros((capacity, fp8) if fp8 == 2 else capacity, dtype=torch.float32, device="cuda")
     else:
         ko = torch.zeros((capacity, d), dtype=torch.bfloat16, device="cuda")
         vo = torch.zeros((capacity, d), dtype=torch.bfloat16, device="cuda")
@@ -35,15 +36,17 @@ def _export(handle, layer, b, h, d, fp8, capacity):
     (64, 4, 16, 64, [5, 1, 1, 90, 300, 1, 7], False),
     (128, 8, 64, 256, [1000, 1, 1, 1, 37], False),
     (128, 2, 0, 3, [2, 9, 1], False),
-    (128, 8, 4, 8, [3, 40, 1, 1, 13], True),
-    (64, 4, 16, 64, [200, 1, 77], True),
+    (128, 8, 4, 8, [3, 40, 1, 1, 13], 1),
+    (64, 4, 16, 64, [200, 1, 77], 1),
+    (128, 8, 4, 8, [3, 40, 1, 1, 13], 2),
+    (64, 4, 16, 64, [200, 1, 77], 2),
 ])
 def test_append_then_export_matches_cache_model(d, hkv, sink, recent, appends, fp8):
     import torch
     batch, layers = 2, 2
     total = sum(appends)
     mask = synth.retrieval_mask(3, layers, hkv, 0.5)
-    handle = duo.duo_cache_create(layers, batch, hkv, hkv, d, sink, recent, total + 5, mask, 1 if fp8 else 0)
+    handle = duo.duo_cache_create(layers, batch, hkv, hkv, d, sink, recent, total + 5, mask, int(fp8))
     try:
         for layer in range(layers):
             k = synth.counter_bf16_batch(11, layer, synth.TENSOR_K, batch, 0, total, hkv, d)
@@ -71,6 +74,13 @@ def test_append_then_export_matches_cache_model(d, hkv, sink, recent, appends, f
                         assert got_pos.tolist() == want_pos
                         if not fp8:
                             assert np.array_equal(gk, want_k) and np.array_equal(gv, want_v)
+                        elif fp8 == 2:
+                            ck, sk, lk = oracle.quantize_rows_int4(synth.bf16_bits_to_f32(want_k))
+                            cv, sv, lv = oracle.quantize_rows_int4(synth.bf16_bits_to_f32(want_v))
+                            assert np.array_equal(gk, oracle.pack_int4(ck)) and np.array_equal(gv, oracle.pack_int4(cv))
+                            for got_par, want_par in ((gks[:, 0], sk), (gks[:, 1], lk), (gvs[:, 0], sv), (gvs[:, 1], lv)):
+                                assert np.array_equal(np.ascontiguousarray(got_par).view(np.uint32),
+                                                      np.ascontiguousarray(want_par).view(np.uint32))
                         else:
                             ck, sk = oracle.quantize_rows(synth.bf16_bits_to_f32(want_k))
                             cv, sv = oracle.quantize_rows(synth.bf16_bits_to_f32(want_v))

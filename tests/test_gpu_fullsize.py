@@ -154,7 +154,7 @@ def _long_context_stack(n_ctx, kv_dtype, n_layers, check_layers, seed):
             if kvh == ret_head:
                 kb = cpu_history_bits(seed, layer, synth.TENSOR_K, 0, n_ctx + 1, hkv, d, heads=[kvh])
                 vb = cpu_history_bits(seed, layer, synth.TENSOR_V, 0, n_ctx + 1, hkv, d, heads=[kvh])
-                k_hist, v_hist = oracle_history_f64(kb, kv_dtype == 1), oracle_history_f64(vb, kv_dtype == 1)
+                k_hist, v_hist = oracle_history_f64(kb, kv_dtype), oracle_history_f64(vb, kv_dtype)
                 del kb, vb
             else:
                 # the oracle masks every other row of a streaming head, so only the rows it can see are
@@ -164,8 +164,8 @@ def _long_context_stack(n_ctx, kv_dtype, n_layers, check_layers, seed):
                 for p0, n in ((0, SINK), (n_ctx + 1 - RECENT, RECENT)):
                     kb = synth.counter_bf16(seed, layer, synth.TENSOR_K, 0, p0, n, hkv, d, heads=[kvh])
                     vb = synth.counter_bf16(seed, layer, synth.TENSOR_V, 0, p0, n, hkv, d, heads=[kvh])
-                    k_hist[p0:p0 + n] = oracle_history_f64(kb, kv_dtype == 1)
-                    v_hist[p0:p0 + n] = oracle_history_f64(vb, kv_dtype == 1)
+                    k_hist[p0:p0 + n] = oracle_history_f64(kb, kv_dtype)
+                    v_hist[p0:p0 + n] = oracle_history_f64(vb, kv_dtype)
             heads = slice(kvh * group, (kvh + 1) * group)
             q_bits = synth.counter_bf16(seed, layer, synth.TENSOR_Q, 0, n_ctx, 1, hq, d)[:, heads]
             _oracle_check(q_bits, k_hist, v_hist, [n_ctx], mask[layer][kvh:kvh + 1], outs[layer][None, heads],
