@@ -119,7 +119,11 @@ int choose_ret_workers(const duo_cache* c, const Layer& L, int64_t units_ret) {
   if (c->user_splits > 0) {
     w = segs * c->user_splits;
   } else {
-    int64_t budget = 256 - (int64_t)L.view.n_str * c->cfg.batch;
+    // bf16 rows: memory-bound, so the compute units that take the short streaming segments are
+    // left out of the count; quantised rows: instruction-bound, every compute unit gets a worker
+    // and the streaming workgroups run as units free up
+    int64_t budget = 256;
+    if (c->cfg.kv_dtype == DUO_KV_BF16) budget -= (int64_t)L.view.n_str * c->cfg.batch;
     if (budget < 128) budget = 128;
     w = segs <= budget ? segs * (budget / segs) : budget;
     const int64_t by_len = total / kMinUnits;

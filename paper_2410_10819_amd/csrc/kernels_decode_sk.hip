@@ -29,14 +29,20 @@
 //     multiplies the score and the V scale the probability of its key.
 //   - int4 caches (value = code * scale + lo per row): a code c becomes the bf16
 //     value 128 + c by OR-ing its nibble into 0x4300, two codes per instruction.
-//     With A = sum_d q_d (128 + c_d) from the matrix core and qsum = sum_d q_d the
-//     score is scale * A + (lo - 128 scale) * qsum; with p' = bf16(p * scale_v)
-//     the output is sum_key p' (128 + c) (matrix core) + sum_key (p (lo_v + 7.5 scale_v)
-//     - 135.5 p'), the second sum one scalar per head; taking the codes' midpoint
-//     out with p' as rounded leaves the rounding of p' acting on c - 7.5 only.  The nibble extraction leaves the eight
-//     values of a dword in the order 0 4 1 5 2 6 3 7; the query operand and the
-//     output index are permuted to match, so no instruction is spent on order.
+//     The K product starts from -128 sum_d q_d, so it yields A = sum_d q_d c_d and
+//     the score is scale_k A + lo_k sum_d q_d.  With p' = bf16(p scale_v) the
+//     output is sum_key p' (128 + c) (matrix core) + sum_key p (lo_v + 7.5 scale_v)
+//     - 135.5 sum_key p', the last two one scalar per head (the sum of p' as
+//     rounded comes from a product with a row of ones): taking the codes' midpoint
+//     out this way leaves the rounding of p' acting on c - 7.5 only.  The nibble
+//     extraction leaves the eight values of a dword in the order 0 4 1 5 2 6 3 7;
+//     the query operand (for K) and the probability operand (for V) are permuted
+//     to match, so no instruction is spent on order.  V rows are staged in LDS as
+//     codes and come back through the 4-bit transposing read, sixteen d by sixteen
+//     (key, row block) pairs per lane group and read.
 #include "duo_internal.h"
+
+#include <type_traits>
 
 namespace duo {
 namespace {
@@ -50,6 +56,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -98,16 +105,21 @@ __device__ inline uint2 e4m3x4_to_bf16x4(uint32_t w) {
 // Eight 4-bit codes (one dword, code j at bits 4 j) -> eight bf16 values 128 + code as four
 // dwords holding the code pairs (0,4) (1,5) (2,6) (3,7).
 __device__ inline uint4 int4x8_to_bf16x8(uint32_t w) {
-  constexpr uint32_t kMask = 0x000F000Fu, kBias = 0x43004300u;   // bf16 0x4300 = 128, one ulp = 1
+  constexpr uint32_t kMask = 0x000F000Fu;
+  // bf16 0x4300 = 128, one ulp = 1.  The bias passes through an empty asm statement so that the
+  // compiler keeps it in a vector register and can fuse each mask-and-bias into one v_and_or_b32
+  // (with two literal constants it emits the two operations separately).  The fused instruction
+  // itself is left to the compiler: it knows the wait states between it and the matrix-core
+  // instructions that read its result, which it cannot know for an instruction inside an asm.
+  uint32_t bias = 0x43004300u;
+  asm volatile("" : "+v"(bias));
   uint4 r;
-  r.x = (w & kMask) | kBias;
-  r.y = ((w >> 4) & kMask) | kBias;
-  r.z = ((w >> 8) & kMask) | kBias;
-  r.w = ((w >> 12) & kMask) | kBias;
+  r.x = (w & kMask) | bias;
+  r.y = ((w >> 4) & kMask) | bias;
+  r.z = ((w >> 8) & kMask) | bias;
+  r.w = ((w >> 12) & kMask) | bias;
   return r;
 }
-// position e of such a group of eight holds element sigma(e)
-__device__ inline int int4_sigma(int e) { return (e >> 1) + 4 * (e & 1); }
 
 // MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 codes + (scale, lo).
 template <int D, int MODE>
@@ -123,6 +135,9 @@ struct Shape {
   static constexpr int KB = MODE == 2 ? 4 : (MODE == 1 ? 8 : 16);   // bytes of K per lane, 16-key group and k-step
   static constexpr int NSC = MODE == 2 ? 2 : 1;      // floats per row in the scale arrays
   __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
+  // int4: V rows are staged as codes (GROW bytes a row); 16-byte pieces swizzled so that the rows one
+  // transposing read touches (keys 4 qd + r and 16 + 4 qd + r) spread over the banks
+  __device__ static inline int c_swz(int row) { return (((row >> 2) & 1) * 2 + ((row >> 4) & 1)) % VPR; }
 };
 
 // Raw registers of one 32-row block as loaded from the cache.
@@ -135,13 +150,17 @@ struct RawBlock {
 };
 
 // Per-key dequantisation parameters of a block in the lane's key order (keys 16 t + 4 qd + r at
-// index 4 t + r).  fp8: ks, vs.  int4: ks, koff = lo_k - 128 ks, vs, vlo = lo_v + 7.5 vs.
+// index 4 t + r), with the softmax scale c = scale * log2(e) folded in.  fp8: ks = c * scale_k,
+// vs = scale_v.  int4: ks = c * scale_k, klo = c * lo_k, vs = scale_v, vlo = lo_v + 7.5 scale_v.
 struct KeyParams {
-  float ks[8], koff[8], vs[8], vlo[8];
+  float ks[8], klo[8], vs[8], vlo[8];
 };
 
+#ifndef DUO_EXP_INT4_OCC
+#define DUO_EXP_INT4_OCC 1
+#endif
 template <int D, int MODE>
-__global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_sk_kernel(DecodeArgs a) {
   using S = Shape<D, MODE>;
   constexpr bool FP8 = MODE == 1, INT4 = MODE == 2, QUANT = MODE != 0;
   constexpr int NKK = S::NKK, NMB = S::NMB, LROW = S::LROW, GROW = S::GROW;
@@ -227,7 +246,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     // ---- query operand: lane (hd, qd) holds q[head hd][32 kk + 8 qd .. + 7]; for an int4 cache,
     // whose lanes load D/4 consecutive codes of a key, q[head hd][(D/4) qd + 8 kk + sigma(0..7)]
     bf16x8 qf[NKK];
-    float qsum_c = 0.f;   // int4: c_scale * sum_d q[head hd][d]
+    float qsum = 0.f;   // int4: sum_d q[head hd][d]
     {
       const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G + (head_ok ? hd : 0)) * D;
 #pragma unroll
@@ -237,16 +256,15 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         if constexpr (INT4) {
           const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-          for (int i = 0; i < 4; ++i) qsum_c += __uint_as_float(w[i] << 16) + __uint_as_float(w[i] & 0xFFFF0000u);
+          for (int i = 0; i < 4; ++i) qsum += __uint_as_float(w[i] << 16) + __uint_as_float(w[i] & 0xFFFF0000u);
           raw = make_uint4(__builtin_amdgcn_perm(raw.z, raw.x, 0x05040100u), __builtin_amdgcn_perm(raw.z, raw.x, 0x07060302u),
                            __builtin_amdgcn_perm(raw.w, raw.y, 0x05040100u), __builtin_amdgcn_perm(raw.w, raw.y, 0x07060302u));
         }
         qf[kk] = __builtin_bit_cast(bf16x8, raw);
       }
       if constexpr (INT4) {
-        qsum_c += __shfl_xor(qsum_c, 16);
-        qsum_c += __shfl_xor(qsum_c, 32);
-        qsum_c *= c_scale;
+        qsum += __shfl_xor(qsum, 16);
+        qsum += __shfl_xor(qsum, 32);
       }
     }
 
@@ -255,7 +273,10 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
 #pragma unroll
     for (int mb = 0; mb < NMB; ++mb) oacc[mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m_ref = -INFINITY, l_lane = 0.f;
-    float corr_lane = 0.f;   // int4: sum over the lane's keys of p (lo_v + 7.5 scale_v) - 135.5 bf16(p scale_v)
+    // int4: corr_lane = sum over the lane's keys of p (lo_v + 7.5 scale_v); pb_sum = sum over all
+    // keys of the head of bf16(p scale_v) as rounded (a matrix-core product with a row of ones)
+    float corr_lane = 0.f;
+    f32x4 pb_sum = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     using Raw = RawBlock<D, MODE>;
     // Loads of a block whose 32 rows are all present: a uniform block address plus per-lane
@@ -346,31 +367,38 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     auto qk = [&](const bf16x8 (&kf)[2][NKK], f32x4 (&sacc)[2]) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        sacc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        // int4 operands are 128 + code: start from -128 sum(q), so the result is sum(q code)
+        const float s0 = INT4 ? -128.f * qsum : 0.f;
+        sacc[t] = (f32x4){s0, s0, s0, s0};
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
           sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][kk], qf[kk], sacc[t], 0, 0, 0);
       }
     };
     // Softmax update and O^T += V^T P^T of one block whose V rows are staged in my_v (bf16).
-    // key_base: row index of the block's first key; keys >= valid_end are masked.
-    auto finish = [&](const f32x4 (&sacc)[2], const KeyParams& kp, int64_t key_base, int64_t valid_end) {
+    // key_base: row index of the block's first key; with `masked`, keys >= valid_end, the excluded
+    // key and the padding heads are masked; without, every key of the block is visible (the padding
+    // heads then carry finite values that are never written out).
+    auto finish = [&](auto masked, const f32x4 (&sacc)[2], const KeyParams& kp, int64_t key_base, int64_t valid_end) {
       float sv[8];
       float lmax = -INFINITY;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int64_t key = key_base + 16 * t + 4 * qd + r;
           float s;
           if constexpr (INT4) {
-            s = sacc[t][r] * (kp.ks[4 * t + r] * c_scale) + kp.koff[4 * t + r] * qsum_c;
+            s = sacc[t][r] * kp.ks[4 * t + r] + kp.klo[4 * t + r] * qsum;
+          } else if constexpr (FP8) {
+            s = sacc[t][r] * kp.ks[4 * t + r];
           } else {
             s = sacc[t][r] * c_scale;
-            if constexpr (FP8) s *= kp.ks[4 * t + r];
           }
-          const bool ok = head_ok && key < valid_end && key != exclude;
-          s = ok ? s : -INFINITY;
+          if constexpr (decltype(masked)::value) {
+            const int64_t key = key_base + 16 * t + 4 * qd + r;
+            const bool ok = head_ok && key < valid_end && key != exclude;
+            s = ok ? s : -INFINITY;
+          }
           sv[4 * t + r] = s;
           lmax = fmaxf(lmax, s);
         }
@@ -381,7 +409,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         const float mu = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = fast_exp2(m_ref - mu);
         l_lane *= alpha;
-        if constexpr (INT4) corr_lane *= alpha;
+        if constexpr (INT4) { corr_lane *= alpha; pb_sum *= alpha; }
 #pragma unroll
         for (int mb = 0; mb < NMB; ++mb) oacc[mb] *= alpha;
         m_ref = m_new;
@@ -392,14 +420,41 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) { p[i] = fast_exp2(sv[i] - mu); psum += p[i]; }
       l_lane += psum;
+      // int4: the code expansion leaves the eight keys of an operand in the order 0 4 1 5 2 6 3 7
       bf16x8 pb;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) pb[i] = (__bf16)(QUANT ? p[i] * kp.vs[i] : p[i]);
+      for (int i = 0; i < 8; ++i) {
+        const int src = INT4 ? (i >> 1) + 4 * (i & 1) : i;
+        pb[i] = (__bf16)(QUANT ? p[src] * kp.vs[src] : p[src]);
+      }
       if constexpr (INT4) {
-        // the matrix core sums pb * (128 + code) = pb * (code - 7.5) + 135.5 pb: take the second
-        // term back exactly as rounded; kp.vlo holds lo + 7.5 scale
+        // the matrix core sums pb * (128 + code) = pb * (code - 7.5) + 135.5 pb: the second term is
+        // taken back at the end exactly as rounded; kp.vlo holds lo + 7.5 scale
 #pragma unroll
-        for (int i = 0; i < 8; ++i) corr_lane += p[i] * kp.vlo[i] - 135.5f * (float)pb[i];
+        for (int i = 0; i < 8; ++i) corr_lane += p[i] * kp.vlo[i];
+        const uint32_t one2 = 0x3F803F80u;
+        pb_sum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, make_uint4(one2, one2, one2, one2)), pb,
+                                                         pb_sum, 0, 0, 0);
+      }
+      if constexpr (INT4) {
+        // O^T += V^T P^T from the staged codes.  The 4-bit transposing read hands lane i of a 16-lane
+        // group nibble i of the 64 bits each lane e of the group points at, as its nibble e.  Lane e
+        // points at the 16 codes of key 16 (j >> 2) + 4 qd + (j & 3), j = e & 7, in the 16-row block
+        // 2 mbp + (e >> 3) of O^T: the first dword read is then row block 2 mbp over the lane group's
+        // eight keys, the second dword row block 2 mbp + 1, and row i of a block is d = 16 block + i.
+        const int j = hd & 7, half = hd >> 3;
+        const int key = 16 * (j >> 2) + 4 * qd + (j & 3);
+        const uint8_t* rowp = my_v + key * GROW + half * 8;
+        const int sw = S::c_swz(key);
+#pragma unroll
+        for (int mbp = 0; mbp < NMB / 2; ++mbp) {
+          const i32x2 t = __builtin_amdgcn_ds_read_tr4_b64_v2i32(LDS_PTR(i32x2, rowp + ((mbp ^ sw) * 16)));
+          const bf16x8 v0 = __builtin_bit_cast(bf16x8, int4x8_to_bf16x8((uint32_t)t[0]));
+          const bf16x8 v1 = __builtin_bit_cast(bf16x8, int4x8_to_bf16x8((uint32_t)t[1]));
+          oacc[2 * mbp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v0, pb, oacc[2 * mbp], 0, 0, 0);
+          oacc[2 * mbp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v1, pb, oacc[2 * mbp + 1], 0, 0, 0);
+        }
+        return;
       }
       // O^T += V^T P^T : lane (hd, qd) supplies the address of key 16 h + 4 qd + (hd >> 2), d 16 mb + 4 (hd & 3)
       const int e = hd >> 2, i4 = hd & 3;
@@ -424,10 +479,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       for (int j = 0; j < S::NV; ++j) {
         const int row = j * S::VRPI + lane / S::VPR, pc = lane % S::VPR;
         if constexpr (INT4) {
-          const uint32_t w[4] = {rb.v[j].x, rb.v[j].y, rb.v[j].z, rb.v[j].w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            *(uint4*)(my_v + row * LROW + (((4 * pc + i) ^ S::v_swz(row)) * 16)) = int4x8_to_bf16x8(w[i]);
+          *(uint4*)(my_v + row * GROW + ((pc ^ S::c_swz(row)) * 16)) = rb.v[j];   // codes as they are
         } else if constexpr (FP8) {
           const uint2 a0 = e4m3x4_to_bf16x4(rb.v[j].x), a1 = e4m3x4_to_bf16x4(rb.v[j].y);
           const uint2 a2 = e4m3x4_to_bf16x4(rb.v[j].z), a3 = e4m3x4_to_bf16x4(rb.v[j].w);
@@ -454,9 +506,10 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       qk(kf, sacc);
       if constexpr (INT4) {
         // [0..31] K scale, [32..63] K lo, [64..95] V scale, [96..127] V lo, each in row order
+        // the lane that loaded a row's parameters folds the constants in before sharing them
         const int at = lane < 32 ? lane : lane + 32;
-        sm_sc[wave][at] = rb.sc[0];
-        sm_sc[wave][at + 32] = rb.sc[1];
+        sm_sc[wave][at] = lane < 32 ? rb.sc[0] * c_scale : rb.sc[0];
+        sm_sc[wave][at + 32] = lane < 32 ? rb.sc[1] * c_scale : rb.sc[1] + 7.5f * rb.sc[0];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const float4 s4 = *(const float4*)&sm_sc[wave][16 * t + 4 * qd];
@@ -464,14 +517,12 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
           const float4 v4 = *(const float4*)&sm_sc[wave][64 + 16 * t + 4 * qd];
           const float4 o4 = *(const float4*)&sm_sc[wave][96 + 16 * t + 4 * qd];
           kp.ks[4 * t] = s4.x; kp.ks[4 * t + 1] = s4.y; kp.ks[4 * t + 2] = s4.z; kp.ks[4 * t + 3] = s4.w;
-          kp.koff[4 * t] = l4.x - 128.f * s4.x; kp.koff[4 * t + 1] = l4.y - 128.f * s4.y;
-          kp.koff[4 * t + 2] = l4.z - 128.f * s4.z; kp.koff[4 * t + 3] = l4.w - 128.f * s4.w;
+          kp.klo[4 * t] = l4.x; kp.klo[4 * t + 1] = l4.y; kp.klo[4 * t + 2] = l4.z; kp.klo[4 * t + 3] = l4.w;
           kp.vs[4 * t] = v4.x; kp.vs[4 * t + 1] = v4.y; kp.vs[4 * t + 2] = v4.z; kp.vs[4 * t + 3] = v4.w;
-          kp.vlo[4 * t] = o4.x + 7.5f * v4.x; kp.vlo[4 * t + 1] = o4.y + 7.5f * v4.y;
-          kp.vlo[4 * t + 2] = o4.z + 7.5f * v4.z; kp.vlo[4 * t + 3] = o4.w + 7.5f * v4.w;
+          kp.vlo[4 * t] = o4.x; kp.vlo[4 * t + 1] = o4.y; kp.vlo[4 * t + 2] = o4.z; kp.vlo[4 * t + 3] = o4.w;
         }
       } else if constexpr (FP8) {
-        sm_sc[wave][lane] = rb.sc[0];
+        sm_sc[wave][lane] = lane < 32 ? rb.sc[0] * c_scale : rb.sc[0];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const float4 kq = *(const float4*)&sm_sc[wave][16 * t + 4 * qd];
@@ -490,7 +541,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     // where they are written.  Then the partly filled last block, if any, by the wavefront whose
     // turn it is.
     const int n_full = (int)((row1 - row0) / kUnit) < nb ? (int)((row1 - row0) / kUnit) : nb;
-    {
+    auto run_blocks = [&](auto masked) {
       Raw r0, r1, r2;
       f32x4 sacc[2];
       KeyParams kp;
@@ -501,7 +552,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         if (prefetch) issue(rb, blk_of(i + 3));
         __builtin_amdgcn_sched_barrier(0);
-        finish(sacc, kp, row0 + (int64_t)blk_of(i) * kUnit, n_rows);
+        finish(masked, sacc, kp, row0 + (int64_t)blk_of(i) * kUnit, n_rows);
         __builtin_amdgcn_sched_barrier(0);
       };
       if (n_my > 0) issue(r0, blk_of(0));
@@ -524,9 +575,12 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       if (n_full < nb && wave == (n_full & 3)) {
         issue_tail(r0, n_full);
         stage_qk(r0, sacc, kp);
-        finish(sacc, kp, row0 + (int64_t)n_full * kUnit, n_rows);
+        finish(std::true_type{}, sacc, kp, row0 + (int64_t)n_full * kUnit, n_rows);
       }
-    }
+    };
+    // full blocks need no masking unless the segment has an excluded key
+    if (exclude < 0) run_blocks(std::false_type{});
+    else run_blocks(std::true_type{});
 
     // ---- the new token (wavefront 0 of the part that ends the segment); with a.commit its rows
     // are also written into the cache
@@ -577,7 +631,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
           }
         }
         kc = int4x8_to_bf16x8(kq);
-        vc = int4x8_to_bf16x8(vq);
+        vc.x = vq;   // V goes to the staging buffer as codes
         ks1 = __shfl(ks1, 0); vs1 = __shfl(vs1, 0);
         klo1 = __shfl(kmin, 0); vlo1 = __shfl(vmin, 0);
       } else if constexpr (!FP8) {
@@ -622,7 +676,11 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       }
       // the (dequantised) bf16 rows through LDS into the operand layouts: K as key 0 of a block
       // whose other keys are masked, V as every row of the staging buffer
-      if (row_lane) { *(uint4*)&sm_new[0][8 * lane] = kc; *(uint4*)&sm_new[1][8 * lane] = vc; }
+      if (row_lane) {
+        *(uint4*)&sm_new[0][8 * lane] = kc;
+        if constexpr (INT4) ((uint32_t*)&sm_new[1][0])[lane] = vc.x;
+        else *(uint4*)&sm_new[1][8 * lane] = vc;
+      }
       bf16x8 kf[2][NKK];
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
@@ -631,19 +689,27 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
         kf[0][kk] = __builtin_bit_cast(bf16x8, x);
         kf[1][kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
       }
+      if constexpr (INT4) {
 #pragma unroll
-      for (int j = 0; j < kUnit * S::CPR / 64; ++j) {
-        const int row = j * (64 / S::CPR) + lane / S::CPR, pc = lane % S::CPR;
-        *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
+        for (int j = 0; j < S::NV; ++j) {
+          const int row = j * S::VRPI + lane / S::VPR, pc = lane % S::VPR;
+          *(uint4*)(my_v + row * GROW + ((pc ^ S::c_swz(row)) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < kUnit * S::CPR / 64; ++j) {
+          const int row = j * (64 / S::CPR) + lane / S::CPR, pc = lane % S::CPR;
+          *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
+        }
       }
       KeyParams kp;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { kp.ks[i] = ks1; kp.vs[i] = vs1; kp.koff[i] = klo1 - 128.f * ks1; kp.vlo[i] = vlo1 + 7.5f * vs1; }
+      for (int i = 0; i < 8; ++i) { kp.ks[i] = ks1 * c_scale; kp.vs[i] = vs1; kp.klo[i] = klo1 * c_scale; kp.vlo[i] = vlo1 + 7.5f * vs1; }
       const int64_t saved = exclude;
       exclude = -1;
       f32x4 sacc[2];
       qk(kf, sacc);
-      finish(sacc, kp, 0, 1);   // keys 0 .. 31 of a virtual block, only key 0 valid
+      finish(std::true_type{}, sacc, kp, 0, 1);   // keys 0 .. 31 of a virtual block, only key 0 valid
       exclude = saved;
     }
 
@@ -654,6 +720,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
     if constexpr (INT4) {
       corr_head = corr_lane + __shfl_xor(corr_lane, 16);
       corr_head += __shfl_xor(corr_head, 32);
+      corr_head -= 135.5f * pb_sum[0];
     }
     __syncthreads();   // every wavefront is done with its V staging buffer
     if (head_ok) {
@@ -661,9 +728,7 @@ __global__ __launch_bounds__(256) void decode_sk_kernel(DecodeArgs a) {
       for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          int pos = 16 * mb + 4 * qd + r;
-          if constexpr (INT4) pos = (pos & ~7) + int4_sigma(pos & 7);   // staged rows hold the code order 0 4 1 5 2 6 3 7
-          sm_o[(wave * 16 + hd) * D + pos] = oacc[mb][r] + corr_head;
+          sm_o[(wave * 16 + hd) * D + 16 * mb + 4 * qd + r] = oacc[mb][r] + corr_head;
         }
       if (qd == 0) { sm_m[wave][hd] = m_ref; sm_l[wave][hd] = l_head; }
     }
