@@ -27,7 +27,8 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, scaled by a 1 GiB
 # device copy (summaries under profiles/); known for these workloads only.
 MEASURED_TRAFFIC = {"c2": {"decode": 139.14e6 + 0.17e6, "prefill": 172.2e6 + 40.8e6},
-                    "c4": {"decode": 2149.2e6 + 0.6e6}}
+                    "c4": {"decode": 2149.2e6 + 0.6e6},
+                    "c6": {"decode": 1902.8e6 + 0.6e6}}
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
@@ -53,6 +54,9 @@ WORKLOADS = {
     "c5": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=3300000, chunk=0, decode=4, batch=1,
                layers=32, kv_dtype=1, desc="Llama-3-8B-shaped GQA decode at 3300000 context, 32 layers, fp8 e4m3 KV "
                                            "+ fp32 scales per (token, KV head), batch 1"),
+    "c6": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=3300000, chunk=0, decode=4, batch=1,
+               layers=32, kv_dtype=2, desc="Llama-3-8B-shaped GQA decode at 3300000 context, 32 layers, 4-bit KV "
+                                           "(asymmetric codes + fp32 scale and minimum per (token, KV head)), batch 1"),
 }
 
 
@@ -220,7 +224,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- algorithmic work
-    row_bytes = d + 4 if kv_dtype else 2 * d
+    row_bytes = {0: 2 * d, 1: d + 4, 2: d // 2 + 8}[kv_dtype]
     n_timed_tokens = n_decode if attn_prefill else n_decode * args.steps
     dec_bytes = []           # per launch (one layer, one token, all sequences)
     for t in range(n_timed_tokens):
@@ -270,7 +274,8 @@ def main():
         "unit": "us/token" if n_decode else "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": False if n_decode else True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if not kv_dtype else "bf16 (fp8 e4m3 KV, fp32 accumulate)", "data": "synthetic",
+        "dtype": {0: "bf16", 1: "bf16 (fp8 e4m3 KV, fp32 accumulate)",
+                  2: "bf16 (int4 KV, fp32 accumulate)"}[kv_dtype], "data": "synthetic",
         "config": {"workload": w["desc"], "name": args.workload, "n_layers": n_layers, "n_q_heads": hq,
                    "n_kv_heads": hkv, "head_dim": d, "retrieval_kv_heads": n_ret, "sink": sink, "recent": recent,
                    "batch": B, "prefill_tokens": n_prefill, "chunk": chunk, "decode_steps": n_decode,
@@ -381,7 +386,7 @@ def cpu_baseline(synth, seed, w, mask, n_ctx, batch):
     import oracle
     from concurrent.futures import ThreadPoolExecutor
     hq, hkv, d, sink, recent = w["hq"], w["hkv"], w["d"], w["sink"], w["recent"]
-    n_layers, fp8 = w.get("layers", 1), w.get("kv_dtype", 0) == 1
+    n_layers, kv_dtype = w.get("layers", 1), w.get("kv_dtype", 0)
     group = hq // hkv
     n_sample = 4 if n_ctx <= 40000 else 1
     t_hist = n_ctx + n_sample
@@ -398,14 +403,18 @@ def cpu_baseline(synth, seed, w, mask, n_ctx, batch):
 
         with ThreadPoolExecutor(8) as pool:
             list(pool.map(job, range(0, t_hist, step)))
-        if not fp8:
+        if not kv_dtype:
             return synth.bf16_bits_to_f64(out)
         deq = np.empty(out.shape, dtype=np.float64)
         qstep = 1 << 14
 
         def qjob(p0):
-            codes, scales = oracle.quantize_rows(synth.bf16_bits_to_f32(out[p0:p0 + qstep]))
-            deq[p0:p0 + qstep] = oracle.dequantize_rows(codes, scales)
+            x = synth.bf16_bits_to_f32(out[p0:p0 + qstep])
+            if kv_dtype == 2:
+                deq[p0:p0 + qstep] = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(x))
+            else:
+                codes, scales = oracle.quantize_rows(x)
+                deq[p0:p0 + qstep] = oracle.dequantize_rows(codes, scales)
 
         with ThreadPoolExecutor(8) as pool:
             list(pool.map(qjob, range(0, t_hist, qstep)))
