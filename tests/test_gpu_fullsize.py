@@ -179,3 +179,8 @@ def test_llama3_8b_shape_decode_at_1m_context_32_layers_bf16():
 
 def test_llama3_8b_shape_decode_at_3300000_context_32_layers_fp8():
     _long_context_stack(3300000, duo.DUO_KV_FP8_E4M3, 32, check_layers=(17,), seed=5)
+
+
+def test_llama3_8b_shape_decode_at_3300000_context_32_layers_int4():
+    # the paper's capacity setting (Section 3.4: 3.3 million tokens with a 4-bit KV cache) at its shape
+    _long_context_stack(3300000, duo.DUO_KV_INT4, 32, check_layers=(9,), seed=6)
