@@ -34,3 +34,7 @@ from .int4_codec import (  # noqa: F401
     pack_int4,
     unpack_int4,
 )
+from .gate_mixed import (  # noqa: F401
+    visible_mask_block,
+    gate_mixed_attention,
+)
