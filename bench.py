@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--splits", type=int, default=0, help="key splits per retrieval head in decode (0 = automatic)")
-    ap.add_argument("--sweep", default=None, choices=["decode_ratio", "decode_context", "prefill_chunk"],
+    ap.add_argument("--sweep", default=None, choices=["decode_ratio", "decode_context", "prefill_chunk", "gate_mixed"],
                     help="instead of the benchmark line, print one JSON line per point of a sweep that mirrors "
                          "the shape of the paper's efficiency figures (latency against retrieval-head ratio, "
                          "context length, pre-filling chunk size), each with the all-retrieval (= full "
@@ -364,6 +364,36 @@ def run_sweep(name, torch, duo, synth, lib, seed):
                 print(json.dumps({"sweep": name, "shape": shape, "context": n_ctx, "retrieval_ratio": n_ret / hkv,
                                   "decode_us": round(us, 2), "full_attention_us": round(full, 2),
                                   "speedup_vs_full": round(full / us, 3)}), flush=True)
+    elif name == "gate_mixed":
+        # identification-phase forward (Section 2.2): alpha * full + (1 - alpha) * streaming over whole
+        # sequences of the training lengths (appendix, Training Hyperparameters), sink 128 / recent 256 as in
+        # Section 3.1, the streaming term with the Lambda mask and with the block-aligned mask (block 128)
+        g_sink, g_recent = 128, 256
+        for shape, lengths in (("mha", (4096, 32000)), ("gqa", (8192, 32000))):
+            hq, hkv = shapes[shape]
+            alpha = np.random.default_rng(seed).uniform(0, 1, hkv).astype(np.float32)
+            h = duo.duo_cache_create(1, 1, hq, hkv, d, g_sink, g_recent, 64, np.ones((1, hkv), dtype=np.uint8))
+            for n in lengths:
+                q, k, v = fill(synth.TENSOR_Q, hq, 0, n), fill(synth.TENSOR_K, hkv, 0, n), fill(synth.TENSOR_V, hkv, 0, n)
+                out, ws = torch.empty_like(q), torch.empty_like(q)
+                full_pairs = hq * n * (n + 1) // 2
+                for block in (0, 128):
+                    ms = timed(lambda: duo.duo_attn_gate_mixed(h, 0, q, k, v, n, alpha, out, ws, block=block), 3)
+                    if block:
+                        n_sb, n_lb = -(-g_sink // block), -(-(g_recent - 1) // block) + 1
+                        i = np.arange(n, dtype=np.int64)
+                        vis = np.minimum(i + 1, np.minimum(n_sb * block, i + 1)
+                                         + np.maximum(0, i + 1 - np.maximum((i // block - n_lb + 1) * block,
+                                                                             np.minimum(n_sb * block, i + 1))))
+                        str_pairs = hq * int(vis.sum())
+                    else:
+                        str_pairs = hq * visible_pairs(0, n, g_sink, g_recent, False)
+                    flops = 4 * d * (full_pairs + str_pairs)
+                    print(json.dumps({"sweep": name, "shape": shape, "tokens": n, "block": block,
+                                      "gate_mixed_ms": round(ms, 3), "tflops": round(flops / ms / 1e9, 1),
+                                      "streaming_share_of_flops": round(str_pairs / (full_pairs + str_pairs), 4)}),
+                          flush=True)
+            duo.duo_cache_destroy(h)
     else:
         for shape, n_ret, n_ctx, chunks in (("mha", 8, 102400, (4096, 8192, 16384, 32768, 102400)),
                                             ("gqa", 4, 327680, (16384, 32768, 65536, 163840))):

@@ -130,6 +130,27 @@ int duo_attn_prefill_deployed(duo_cache_t* cache, int layer, const void* q, cons
                               const void* v, int n_new, const duo_call_params_t* params,
                               void* out, float* lse, void* stream);
 
+/* Gate-mixed attention forward of the identification phase (Section 2.2, Optimization-based
+ * Identification): for every KV head g with gate alpha[g] in [0, 1] and every query head of its
+ * group,  out = alpha[g] * full_attn + (1 - alpha[g]) * streaming_attn  over a whole sequence of
+ * n_tokens positions, with full_attn causal and streaming_attn restricted to the cache's sink and
+ * recent constants.  No KV cache is read or written: the handle supplies the geometry (batch,
+ * heads, head_dim, sink, recent, scale) only, and the layer's head classes play no part.
+ * q: [batch, n_tokens, n_q_heads, head_dim]; k, v: [batch, n_tokens, n_kv_heads, head_dim];
+ * alpha: HOST fp32 [n_kv_heads] (n_kv_heads <= 64), read before the call returns.
+ * block = 0: streaming_attn uses the Lambda mask.  block >= 1: the
+ * block-aligned approximation the appendix (Experimental Details) mentions for training: query i
+ * sees key j <= i iff block j / block is among the first ceil(sink / block) blocks or fewer than
+ * ceil((recent - 1) / block) + 1 blocks before block i / block (the paper shows the pattern in a
+ * figure only; this is the smallest block-aligned mask of that shape containing the Lambda mask).
+ * out: bf16, shape of q.  workspace: DEVICE buffer of the size of out, overwritten (it holds the
+ * streaming term between the two attention launches and the mixing launch).
+ * DUO_EINVAL for NULL pointers, n_tokens < 1, n_kv_heads > 64, a gate outside [0, 1] or a
+ * negative block. */
+int duo_attn_gate_mixed(duo_cache_t* cache, int layer, const void* q, const void* k, const void* v,
+                        int n_tokens, const float* alpha, int block, void* out, void* workspace,
+                        void* stream);
+
 /* One decoding step (Section 2.3, Decoding).  q: [batch, 1, n_q_heads, head_dim].
  * If k and v are NULL the new token has already been appended and the query sits
  * at position len-1.  If both are given ([batch, 1, n_kv_heads, head_dim]) they

@@ -65,6 +65,7 @@ def load() -> ctypes.CDLL:
     lib.duo_kv_append.argtypes = [vp, i32, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp]
     lib.duo_attn_prefill.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
     lib.duo_attn_prefill_deployed.argtypes = lib.duo_attn_prefill.argtypes
+    lib.duo_attn_gate_mixed.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float), i32, vp, vp, vp]
     lib.duo_attn_decode.argtypes = [vp, i32, vp, vp, vp, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
     lib.duo_decode_step.argtypes = lib.duo_attn_decode.argtypes
     lib.duo_cache_export.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, ctypes.POINTER(i64), vp]
@@ -193,6 +194,17 @@ def duo_attn_prefill_deployed(cache, layer, q, k, v, n_new, out, lse=None, param
     _check(load().duo_attn_prefill_deployed(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
                                             _ptr(v, "v", torch.bfloat16), n_new, pp, _ptr(out, "out", torch.bfloat16),
                                             _ptr(lse, "lse", torch.float32), _stream(stream)))
+
+
+def duo_attn_gate_mixed(cache, layer, q, k, v, n_tokens, alpha, out, workspace, block=0, stream=None):
+    """alpha: host float32 values, one per KV head; workspace: device buffer of out's size."""
+    import torch
+    al = np.ascontiguousarray(np.asarray(alpha, dtype=np.float32))
+    _check(load().duo_attn_gate_mixed(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
+                                      _ptr(v, "v", torch.bfloat16), n_tokens,
+                                      al.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), block,
+                                      _ptr(out, "out", torch.bfloat16), _ptr(workspace, "workspace", torch.bfloat16),
+                                      _stream(stream)))
 
 
 def duo_attn_decode(cache, layer, q, out, k=None, v=None, lse=None, params=None, stream=None):

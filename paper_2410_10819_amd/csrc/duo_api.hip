@@ -328,6 +328,7 @@ static int prefill_common(duo_cache_t* c, int layer, const void* q, const void* 
   duo::PrefillArgs a;
   a.lv = L.view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
   a.chunk_causal = chunk_causal ? 1 : 0;
+  a.force_class = 0; a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
   hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "prefill launch");
   return DUO_OK;
@@ -341,6 +342,46 @@ int duo_attn_prefill(duo_cache_t* c, int layer, const void* q, const void* k, co
 int duo_attn_prefill_deployed(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
                               int n_new, const duo_call_params_t* params, void* out, float* lse, void* stream) {
   return prefill_common(c, layer, q, k, v, n_new, params, out, lse, stream, true);
+}
+
+int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k, const void* v, int n_tokens,
+                        const float* alpha, int block, void* out, void* workspace, void* stream) {
+  int rc = check_handle_layer(c, layer);
+  if (rc != DUO_OK) return rc;
+  if (!q || !k || !v || !alpha || !out || !workspace)
+    return fail(DUO_EINVAL, "q, k, v, alpha, out and workspace must not be NULL");
+  if (n_tokens < 1) return fail(DUO_EINVAL, "n_tokens must be >= 1 (got %d)", n_tokens);
+  if (c->cfg.n_kv_heads > duo::kMaxGateHeads)
+    return fail(DUO_EINVAL, "gate-mixed attention supports at most %d KV heads (got %d)", duo::kMaxGateHeads,
+                c->cfg.n_kv_heads);
+  if (block < 0) return fail(DUO_EINVAL, "block must be >= 0 (got %d)", block);
+  for (int g = 0; g < c->cfg.n_kv_heads; ++g)
+    if (!(alpha[g] >= 0.0f && alpha[g] <= 1.0f))
+      return fail(DUO_EINVAL, "alpha[%d] = %g is outside [0, 1]", g, (double)alpha[g]);
+  Layer& L = c->layers[layer];
+  duo::PrefillArgs a;
+  a.lv = L.view; a.q = q; a.k = k; a.v = v; a.lse = nullptr; a.pos0 = 0; a.n = n_tokens; a.chunk_causal = 0;
+  a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
+  // full attention of every head into out
+  a.out = out; a.force_class = 1;
+  hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "gate-mixed full-attention launch");
+  // streaming attention of every head into the workspace
+  a.out = workspace; a.force_class = 2;
+  if (block >= 1) {
+    a.win_block = block;
+    a.sink_eff = (c->cfg.sink + block - 1) / block * block;
+    a.n_local_blocks = (c->cfg.recent - 1 + block - 1) / block + 1;
+  }
+  e = duo::launch_prefill(a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "gate-mixed streaming-attention launch");
+  duo::GateMixArgs m;
+  m.out = out; m.other = workspace; m.rows = (int64_t)c->cfg.batch * n_tokens;
+  m.n_q_heads = c->cfg.n_q_heads; m.group = c->cfg.n_q_heads / c->cfg.n_kv_heads; m.head_dim = c->cfg.head_dim;
+  for (int g = 0; g < duo::kMaxGateHeads; ++g) m.alpha[g] = g < c->cfg.n_kv_heads ? alpha[g] : 0.0f;
+  e = duo::launch_gate_mix(m, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "gate-mix launch");
+  return DUO_OK;
 }
 
 static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,

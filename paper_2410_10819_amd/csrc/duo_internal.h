@@ -76,7 +76,25 @@ struct PrefillArgs {
   int64_t pos0;        // tokens in the cache = position of the chunk's first query
   int32_t n;           // chunk length
   int32_t chunk_causal;  // streaming heads: causal attention over [retained cache || chunk] instead of the Lambda mask
+  // Whole-sequence forward without a cache (pos0 = 0): treat every head as a retrieval head (1) or
+  // as a streaming head (2) whatever the layer's classes are; 0 = use the layer's classes.
+  int32_t force_class;
+  // Streaming heads with force_class = 2: block size of the block-aligned approximation of the
+  // Lambda mask (0 = the Lambda mask itself), the number of sink positions it makes visible
+  // (ceil(sink / block) * block) and the number of key blocks ending at the query's own block.
+  int32_t win_block, sink_eff, n_local_blocks;
 };
+
+// out = alpha[kv head] * out + (1 - alpha[kv head]) * other, bf16 [rows][n_q_heads][head_dim]
+constexpr int kMaxGateHeads = 64;
+struct GateMixArgs {
+  void* out;
+  const void* other;
+  int64_t rows;          // batch * tokens
+  int32_t n_q_heads, group, head_dim;
+  float alpha[kMaxGateHeads];
+};
+hipError_t launch_gate_mix(const GateMixArgs& a, hipStream_t stream);
 
 hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int64_t pos0,
                          int n_new, hipStream_t stream);

@@ -168,18 +168,28 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   const int n_rb = (a.n + BM - 1) / BM;
   // Work list.  Workgroups are dealt to the 8 accelerator dies (each with its own L2) round-robin
   // by block index.  The work is cut into "bundles" of kBundle workgroups that read the same K/V:
-  // the G query heads of one KV head times kBundle / G neighbouring row blocks.  Bundles are
-  // ordered retrieval KV heads first, longest rows first, and dealt to the dies round-robin, so
-  // every die gets the same mix of long and short work while the workgroups running on it at any
-  // time stream the same tiles at about the same time and share them through that die's L2.
+  // the G query heads of one KV head times kBundle / G neighbouring row blocks; a die runs one
+  // bundle at a time, so the workgroups on it stream the same tiles at about the same time and
+  // share them through that die's L2.  Bundles are ranked by length - causal (retrieval) heads
+  // before streaming heads, longest rows first, heads of equal length next to each other - and
+  // dealt to the dies eight at a time in alternating direction, so that every die gets the same
+  // amount of long and short work whatever the number of row blocks and heads is.
   int h, rb;
   {
     const int die = (int)blockIdx.x % kDies, idx = (int)blockIdx.x / kDies;
-    const int bundle = (idx / kBundle) * kDies + die, w = idx % kBundle;
+    const int round = idx / kBundle, w = idx % kBundle;
+    const int rank = round * kDies + ((round & 1) ? kDies - 1 - die : die);
     const int rb_per_bundle = kBundle / lv.group;
     const int bundles_per_head = (n_rb + rb_per_bundle - 1) / rb_per_bundle;
-    if (bundle >= lv.n_kv_heads * bundles_per_head) return;
-    const int kv_slot = bundle / bundles_per_head, c = bundle % bundles_per_head;
+    if (rank >= lv.n_kv_heads * bundles_per_head) return;
+    const int n_heavy = a.force_class == 1 ? lv.n_kv_heads : (a.force_class == 2 ? 0 : lv.n_ret);
+    int kv_slot, c;
+    if (rank < n_heavy * bundles_per_head) {
+      c = rank / n_heavy; kv_slot = rank % n_heavy;
+    } else {
+      const int r2 = rank - n_heavy * bundles_per_head, n_light = lv.n_kv_heads - n_heavy;
+      c = r2 / n_light; kv_slot = n_heavy + r2 % n_light;
+    }
     const int rbi = c * rb_per_bundle + w / lv.group;
     if (rbi >= n_rb) return;
     const int kv = kv_slot < lv.n_ret ? lv.ret_heads[kv_slot] : lv.str_heads[kv_slot - lv.n_ret];
@@ -192,7 +202,9 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   const int slot_head = (int)(info & ~kRetrievalBit);
 
   KeySource ks;
-  ks.retrieval = (info & kRetrievalBit) != 0;
+  ks.retrieval = a.force_class ? a.force_class == 1 : (info & kRetrievalBit) != 0;
+  // sink positions of the streaming list; the block-aligned mask widens them to whole blocks
+  const int sink_k = a.win_block ? a.sink_eff : lv.sink;
   ks.pos0 = a.pos0;
   ks.sink = lv.sink; ks.recent = lv.recent; ks.row_bytes = lv.row_bytes; ks.ring0 = 0;
   ks.chunk_stride = (int64_t)lv.n_kv_heads * D * 2;
@@ -214,7 +226,7 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   }
   const int gap32 = (int)(ks.tail_pos - ks.n_head);
   // list entries below sink_u are sink positions
-  const int64_t sink_u = gap32 == 0 ? (lv.sink < ks.total ? (int64_t)lv.sink : ks.total) : ks.n_head;
+  const int64_t sink_u = gap32 == 0 ? (sink_k < ks.total ? (int64_t)sink_k : ks.total) : ks.n_head;
 
   // Rows of this workgroup / wavefront / lane: sub-block sb covers chunk rows row_w + 32*sb + col.
   const int i_first = rb * BM;
@@ -240,9 +252,11 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   if (causal_list) {
     tA_end = 0; tB_begin = 0; t_end = (qpos_last - gap) / BN + 1;
   } else {
-    const int64_t usink = (int64_t)lv.sink < qpos_last + 1 ? lv.sink : qpos_last + 1;
+    const int64_t usink = (int64_t)sink_k < qpos_last + 1 ? sink_k : qpos_last + 1;
     tA_end = (usink + BN - 1) / BN;
-    int64_t plo = qpos_first - lv.recent + 1;
+    // first window position of the workgroup's first query (window starts never decrease with the query)
+    int64_t plo = a.win_block ? (qpos_first / a.win_block - a.n_local_blocks + 1) * (int64_t)a.win_block
+                              : qpos_first - lv.recent + 1;
     if (plo < 0) plo = 0;
     const int64_t u_lo = plo < ks.tail_pos ? (plo < ks.n_head ? plo : ks.n_head) : ks.n_head + (plo - ks.tail_pos);
     const int64_t u_hi = qpos_last < ks.n_head ? qpos_last : ks.n_head + (qpos_last - ks.tail_pos);
@@ -508,13 +522,17 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
         } else {
           const int nh_rel = clamp_i32(ks.n_head - ub);
           const int sink_rel = clamp_i32(sink_u - ub);
+          // keys at distance < win from the query are inside its window: `recent` for the Lambda mask,
+          // up to the start of the first local block for the block-aligned one
+          const int win = a.win_block ? (int)(qpos[sb] % a.win_block) + (a.n_local_blocks - 1) * a.win_block + 1
+                                      : lv.recent;
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int u_rel = 32 * kb + 8 * (r / 4) + 4 * half + (r % 4);
               const int diff = qa - u_rel - (u_rel >= nh_rel ? gap32 : 0);   // query pos - key pos
-              const bool vis = u_rel < lim && diff >= 0 && (u_rel < sink_rel || diff < lv.recent);
+              const bool vis = u_rel < lim && diff >= 0 && (u_rel < sink_rel || diff < win);
               if (!vis) sv[kb][r] = -INFINITY;
             }
         }
@@ -653,7 +671,35 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
 #define DUO_EXP_NSB 1
 #endif
 
+// out = alpha * out + (1 - alpha) * other, eight bf16 values per thread
+__global__ __launch_bounds__(256) void gate_mix_kernel(GateMixArgs a) {
+  const int64_t pieces_per_row = (int64_t)a.n_q_heads * a.head_dim / 8;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= a.rows * pieces_per_row) return;
+  const int h = (int)((idx % pieces_per_row) / (a.head_dim / 8));
+  const float al = a.alpha[h / a.group], be = 1.0f - al;
+  uint4 x = ((const uint4*)a.out)[idx];
+  const uint4 y = ((const uint4*)a.other)[idx];
+  uint32_t* xw = (uint32_t*)&x;
+  const uint32_t* yw = (const uint32_t*)&y;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = al * __uint_as_float(xw[i] << 16) + be * __uint_as_float(yw[i] << 16);
+    const float hi = al * __uint_as_float(xw[i] & 0xFFFF0000u) + be * __uint_as_float(yw[i] & 0xFFFF0000u);
+    const bf16x2 pr = {(__bf16)lo, (__bf16)hi};   // round to nearest even
+    xw[i] = __builtin_bit_cast(uint32_t, pr);
+  }
+  ((uint4*)a.out)[idx] = x;
+}
+
 }  // namespace
+
+hipError_t launch_gate_mix(const GateMixArgs& a, hipStream_t stream) {
+  const int64_t n = a.rows * a.n_q_heads * a.head_dim / 8;
+  if (n <= 0) return hipSuccess;
+  gate_mix_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+  return hipGetLastError();
+}
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   constexpr int NSB = DUO_EXP_NSB;
@@ -662,7 +708,8 @@ hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   return launch_one<64, 1, NSB>(a, stream);
 #else
   // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
-  const int64_t heavy_blocks = (int64_t)a.lv.batch * a.lv.n_ret * a.lv.group * ((a.n + 255) / 256);
+  const int n_heavy_heads = a.force_class == 1 ? a.lv.n_kv_heads : (a.force_class == 2 ? 0 : a.lv.n_ret);
+  const int64_t heavy_blocks = (int64_t)a.lv.batch * n_heavy_heads * a.lv.group * ((a.n + 255) / 256);
   const bool split_keys = heavy_blocks < 384;
   if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB>(a, stream) : launch_one<128, 1, NSB>(a, stream);
   return split_keys ? launch_one<64, 2, NSB>(a, stream) : launch_one<64, 1, NSB>(a, stream);
