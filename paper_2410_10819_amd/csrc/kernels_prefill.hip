@@ -53,8 +53,16 @@ constexpr int kDies = 8;      // accelerator dies (XCDs), each with its own L2
 constexpr int kBundle = 32;   // workgroups per bundle = compute units per die
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ inline float swap_halves(float x, int peer_byte_addr) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(peer_byte_addr, __builtin_bit_cast(int, x)));
+// The values of lane l and lane l ^ 32, in some order, with one vector instruction and no LDS
+// round trip: v_permlane32_swap exchanges the upper half of its first operand with the lower half
+// of its second.  Written as assembly because this compiler's builtin returns the first result
+// twice; the no-ops cover the wait states around a lane swap whose operands come from, and go to,
+// ordinary vector instructions (never to a matrix-core instruction directly).
+struct HalfPair { float a, b; };
+__device__ inline HalfPair both_halves(float x) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return HalfPair{a, b};
 }
 #ifndef DUO_EXP_PRIO_M
 #define DUO_EXP_PRIO_M 0
@@ -164,7 +172,6 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave / WPG, wig = wave % WPG;
   const int col = lane & 31, half = lane >> 5;
-  const int peer = ((lane ^ 32) << 2);
   const int n_rb = (a.n + BM - 1) / BM;
   // Work list.  Workgroups are dealt to the 8 accelerator dies (each with its own L2) round-robin
   // by block index.  The work is cut into "bundles" of kBundle workgroups that read the same K/V:
@@ -469,13 +476,19 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, score(kb, r));
-        mx = fmaxf(mx, swap_halves(mx, peer));
+        {
+          const HalfPair hp = both_halves(mx);
+          mx = fmaxf(hp.a, hp.b);
+        }
         const float m_new = fmaxf(m_i[sb], mx * sc);
         const float mu = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = fast_exp2(m_i[sb] - mu);
         m_i[sb] = m_new;
-        float psum = 0.f;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        // The row sum is four chains of plain additions of the unrounded probabilities.  A
+        // dot-product instruction per pair would halve the count, but dot products run on the
+        // matrix pipeline and wait while the SIMD's other wavefront has MFMAs in flight, whereas
+        // v_add / v_fma / v_exp / v_max3 / v_cvt_pk issue beside them (measured with a probe).
+        float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -483,12 +496,12 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
             const float p0 = fast_exp2(fmaf(score(kb, r), sc, -mu));
             const float p1 = fast_exp2(fmaf(score(kb, r + 1), sc, -mu));
             const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
-            // the row sum is taken over the rounded probabilities the PV product uses
-            psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);
+            psum[(r / 2) & 1] += p0;
+            psum[2 + ((r / 2) & 1)] += p1;
             pf[sb][kb * 2 + r / 8][r % 8] = pp[0];
             pf[sb][kb * 2 + r / 8][r % 8 + 1] = pp[1];
           }
-        l_i[sb] = l_i[sb] * alpha + psum;
+        l_i[sb] = l_i[sb] * alpha + ((psum[0] + psum[1]) + (psum[2] + psum[3]));
         if (__ballot(alpha != 1.0f) != 0) {
 #pragma unroll
           for (int mb = 0; mb < NMB; ++mb)
@@ -591,7 +604,10 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
 
   // Row sums over both lane halves.
 #pragma unroll
-  for (int sb = 0; sb < NSB; ++sb) l_i[sb] += swap_halves(l_i[sb], peer);
+  for (int sb = 0; sb < NSB; ++sb) {
+    const HalfPair hp = both_halves(l_i[sb]);
+    l_i[sb] = hp.a + hp.b;
+  }
 
   if constexpr (NG == 2) {
     // Key group 1 hands its partial (O, m, l) to key group 0 through LDS.
