@@ -21,10 +21,9 @@
 // to bf16, exactly the B operand of O^T += V^T P^T.  V^T fragments come from LDS
 // transpose reads.  A wavefront alternates a matrix-core block (PV of the previous
 // tile, QK^T of the current one, operand reads pipelined ahead of the products)
-// with the softmax of the current tile; the two wavefronts of a SIMD run half an
-// iteration apart.  (On this part matrix-core and vector-unit instructions of the
-// two wavefronts do not overlap in time - the phases add up - so what counts is
-// the instruction count of the softmax and of the bookkeeping around it.)
+// with the softmax of the current tile; the two wavefronts of a SIMD do the two in
+// opposite order between two workgroup barriers, so that one's softmax runs beside
+// the other's matrix-core block (see the main loop).
 //
 // Keys are addressed through a "virtual key list" so that both head classes
 // share the code: for a retrieval head it is positions 0 .. pos0+n-1 (cache
@@ -64,10 +63,6 @@ __device__ inline HalfPair both_halves(float x) {
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
   return HalfPair{a, b};
 }
-#ifndef DUO_EXP_PRIO_M
-#define DUO_EXP_PRIO_M 0
-#define DUO_EXP_PRIO_S 3
-#endif
 #ifndef DUO_EXP_NW
 #define DUO_EXP_NW 8
 #endif
@@ -555,18 +550,17 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
   };
 
   // Main loop.  A wavefront's work on tile t is M_t = [O += P V of tile t-1, then S = K Q^T of
-  // tile t] (matrix cores) followed by S_t = softmax of tile t (vector unit).  The two wavefronts
-  // of every SIMD run half an iteration apart ("set B" starts one barrier interval later), so
-  // while one is in its matrix-core block the other does its softmax; a barrier ends every
-  // interval.  K runs one tile ahead of V in the LDS buffers: load L_j = (K of tile j, V of tile
-  // j-1) must have landed before interval 2j.  With one key group the eight wavefronts share the
-  // tiles, and set B issues its share of the loads in its softmax half ("B style") so that both
-  // sets have two full intervals of latency; with two key groups each set owns its tiles.
-  // (With one wavefront per SIMD - 64 rows each - there is nothing to alternate with: all
-  // wavefronts run in phase and one barrier per iteration publishes the loads.)
-  constexpr bool kPingPong = NW == 8;
-  const bool set_b = kPingPong && (NG == 1 ? (wave >= NW / 2) : (grp == 1));
-  const bool b_style = NG == 1 && set_b;
+  // tile t] (matrix cores) followed by S_t = softmax of tile t (vector unit).  Every wavefront
+  // passes one workgroup barrier per iteration, but not at the same place: the first wavefront
+  // of a SIMD after its softmax, the second one after its matrix-core block.  Between two
+  // barriers the first therefore runs [M_t, S_t] and the second [S_t-1, M_t]: while one is in
+  // its matrix-core block the other does its softmax, with nothing holding them in lock-step
+  // inside the interval.  (A barrier after each of the two phases makes the two take the plain
+  // sum of their times on this hardware; so does running both in phase.)  K runs one tile ahead
+  // of V in the LDS buffers: load L_j = (K of tile j, V of tile j-1) is issued at the top of
+  // iteration j-1, each wavefront waits for its own loads before its barrier, and the buffer it
+  // overwrites was last read in iteration j-2 by either kind of wavefront.  With 64 rows per
+  // wavefront (one per SIMD) there is nothing to alternate with and all barriers coincide.
   auto kbuf = [&](int j) { return smem + (grp * 2 + (j & 1)) * BUF_BYTES; };
   auto vbuf = [&](int j) { return smem + (grp * 2 + (j & 1)) * BUF_BYTES + TILE; };
   auto issue_l = [&](int j) {
@@ -574,33 +568,32 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
     if (sk < n_tiles) fetch_one(tile_of(sk), kbuf(j), std::false_type{});
     if (j >= 1 && sv < n_tiles) fetch_one(tile_of(sv), vbuf(j - 1), std::true_type{});
   };
-  issue_l(0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's LDS-direct loads have landed
-  __builtin_amdgcn_s_barrier();
-  if (set_b) {
-    if (b_style) issue_l(1);
+  {
+    const bool s_first = NW == 8 && (NG == 1 ? (wave >= NW / 2) : (grp == 1));
+    issue_l(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
-  }
-  for (int it = 0; it <= n_iter; ++it) {
-    const int s = it * NG + grp;
-    const bool live_qk = it < n_iter && s < n_tiles;
-    const bool live_pv = it >= 1 && s - NG < n_tiles;
-    if (!b_style) issue_l(it + 1);
-    __builtin_amdgcn_s_setprio(DUO_EXP_PRIO_M);
-    m_phase(vbuf(it - 1), kbuf(it), live_pv, live_qk);
-    __builtin_amdgcn_s_setprio(DUO_EXP_PRIO_S);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (kPingPong) {
-      if (b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
-      __builtin_amdgcn_s_barrier();
-      if (b_style) issue_l(it + 2);
+    for (int it = 0; it <= n_iter; ++it) {
+      const int s = it * NG + grp;
+      const bool live_qk = it < n_iter && s < n_tiles;
+      const bool live_pv = it >= 1 && s - NG < n_tiles;
+      issue_l(it + 1);
+      m_phase(vbuf(it - 1), kbuf(it), live_pv, live_qk);
+      __builtin_amdgcn_sched_barrier(0);
+      // the iteration's one barrier: after the matrix-core block for the wavefronts that run the
+      // softmax first, after the softmax for the others
+      if (s_first) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+      }
+      if (live_qk) softmax_phase(tile_of(s));
+      __builtin_amdgcn_sched_barrier(0);
+      if (!s_first) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+      }
     }
-    if (live_qk) softmax_phase(tile_of(s));
-    __builtin_amdgcn_sched_barrier(0);
-    if (!b_style) __builtin_amdgcn_s_waitcnt(0x0F70);
-    __builtin_amdgcn_s_barrier();
   }
-  if (kPingPong && !set_b) __builtin_amdgcn_s_barrier();
 
   // Row sums over both lane halves.
 #pragma unroll
