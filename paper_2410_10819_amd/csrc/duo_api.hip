@@ -176,7 +176,7 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   c->layers.resize(cfg->n_layers);
 
   const int sc_per_row = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? 1 : (cfg->kv_dtype == DUO_KV_INT4 ? 2 : 0);
-  const bool fp8 = sc_per_row > 0;   // any quantised mode: scale arrays are allocated
+  const bool quantised = sc_per_row > 0;   // scale arrays are allocated
   const int row_bytes = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? cfg->head_dim
                         : (cfg->kv_dtype == DUO_KV_INT4 ? cfg->head_dim / 2 : cfg->head_dim * 2);
   const int64_t str_rows = (int64_t)cfg->sink + cfg->recent;
@@ -224,8 +224,8 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
     struct { void** p; size_t bytes; bool needed; } want[] = {
         {(void**)&v.k_ret, ret_bytes, n_ret > 0}, {(void**)&v.v_ret, ret_bytes, n_ret > 0},
         {(void**)&v.k_str, str_bytes, n_str > 0}, {(void**)&v.v_str, str_bytes, n_str > 0},
-        {(void**)&v.ks_ret, ret_sc, fp8 && n_ret > 0}, {(void**)&v.vs_ret, ret_sc, fp8 && n_ret > 0},
-        {(void**)&v.ks_str, str_sc, fp8 && n_str > 0}, {(void**)&v.vs_str, str_sc, fp8 && n_str > 0}};
+        {(void**)&v.ks_ret, ret_sc, quantised && n_ret > 0}, {(void**)&v.vs_ret, ret_sc, quantised && n_ret > 0},
+        {(void**)&v.ks_str, str_sc, quantised && n_str > 0}, {(void**)&v.vs_str, str_sc, quantised && n_str > 0}};
     for (auto& w : want) {
       if (!w.needed) continue;
       e = dev_alloc(c, w.p, w.bytes);
@@ -402,7 +402,7 @@ static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k
   a.splits = choose_splits(c, L, L.len);
   a.commit = commit ? 1 : 0;
   hipError_t e;
-  // one query head per KV head on a bf16 cache: the vector-unit kernel; query groups and fp8
+  // one query head per KV head on a bf16 cache: the vector-unit kernel; query groups and quantised
   // caches: the matrix-core kernel
   const bool use_sk = c->force_matrix_decode || L.view.group >= 2 || c->cfg.kv_dtype != DUO_KV_BF16;
   if (use_sk) {
@@ -438,8 +438,8 @@ int duo_cache_export(duo_cache_t* c, int layer, int batch_idx, int kv_head, void
   if (batch_idx < 0 || batch_idx >= c->cfg.batch) return fail(DUO_ERANGE, "batch_idx %d outside [0, %d)", batch_idx, c->cfg.batch);
   if (kv_head < 0 || kv_head >= c->cfg.n_kv_heads) return fail(DUO_ERANGE, "kv_head %d outside [0, %d)", kv_head, c->cfg.n_kv_heads);
   if (!k_out || !v_out || !positions_out || !count_out) return fail(DUO_EINVAL, "k_out, v_out, positions_out and count_out must not be NULL");
-  const bool fp8 = c->cfg.kv_dtype != DUO_KV_BF16;
-  if (fp8 && (!kscale_out || !vscale_out)) return fail(DUO_EINVAL, "scale outputs are required for a quantised cache");
+  const bool quantised = c->cfg.kv_dtype != DUO_KV_BF16;
+  if (quantised && (!kscale_out || !vscale_out)) return fail(DUO_EINVAL, "scale outputs are required for a quantised cache");
   Layer& L = c->layers[layer];
   int64_t count = L.mask[kv_head] ? L.len : duo::streaming_rows(L.len, c->cfg.sink, c->cfg.recent);
   if (count > capacity) return fail(DUO_ERANGE, "export needs %lld rows but capacity is %lld", (long long)count, (long long)capacity);
