@@ -37,4 +37,5 @@ from .int4_codec import (  # noqa: F401
 from .gate_mixed import (  # noqa: F401
     visible_mask_block,
     gate_mixed_attention,
+    gate_mixed_rows,
 )

@@ -44,28 +44,36 @@ def _attend(qv, keys, vals, scale):
     return (e / e.sum()) @ vals
 
 
-def gate_mixed_attention(q, k, v, alpha, sink, recent, scale=None, block=0):
-    """q [T, Hq, D], k/v [T, Hkv, D], alpha [Hkv] -> out [T, Hq, D] (float64).
+def gate_mixed_rows(q_rows, k, v, alpha, positions, sink, recent, scale=None, block=0):
+    """Rows `positions` of the gate-mixed forward: q_rows [n, Hq, D] are the queries at those positions,
+    k/v [T, Hkv, D] the whole sequence, alpha [Hkv] -> out [n, Hq, D] (float64).
 
     Query head h uses KV head g = h // (Hq / Hkv) and that head's gate.  block = 0: the streaming term
     uses the Lambda mask; block >= 1: its block-sparse approximation.
     """
-    q = np.asarray(q, dtype=np.float64)
+    q_rows = np.asarray(q_rows, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     alpha = np.asarray(alpha, dtype=np.float64)
-    t_len, hq, d = q.shape
+    n, hq, d = q_rows.shape
     hkv = k.shape[1]
-    assert hq % hkv == 0 and alpha.shape == (hkv,)
+    assert hq % hkv == 0 and alpha.shape == (hkv,) and len(positions) == n
     group = hq // hkv
     if scale is None:
         scale = 1.0 / np.sqrt(d)
-    out = np.zeros((t_len, hq, d))
-    for i in range(t_len):
+    out = np.zeros((n, hq, d))
+    for r, i in enumerate(positions):
+        i = int(i)
         vis = visible_mask(i, sink, recent, False) if block == 0 else visible_mask_block(i, sink, recent, block)
         for h in range(hq):
             g = h // group
-            full = _attend(q[i, h], k[: i + 1, g], v[: i + 1, g], scale)
-            stream = _attend(q[i, h], k[: i + 1, g][vis], v[: i + 1, g][vis], scale)
-            out[i, h] = alpha[g] * full + (1.0 - alpha[g]) * stream
+            full = _attend(q_rows[r, h], k[: i + 1, g], v[: i + 1, g], scale)
+            stream = _attend(q_rows[r, h], k[: i + 1, g][vis], v[: i + 1, g][vis], scale)
+            out[r, h] = alpha[g] * full + (1.0 - alpha[g]) * stream
     return out
+
+
+def gate_mixed_attention(q, k, v, alpha, sink, recent, scale=None, block=0):
+    """The whole forward: q [T, Hq, D], k/v [T, Hkv, D], alpha [Hkv] -> out [T, Hq, D] (float64)."""
+    q = np.asarray(q, dtype=np.float64)
+    return gate_mixed_rows(q, k, v, alpha, np.arange(q.shape[0]), sink, recent, scale, block)

@@ -184,3 +184,34 @@ def test_llama3_8b_shape_decode_at_3300000_context_32_layers_fp8():
 def test_llama3_8b_shape_decode_at_3300000_context_32_layers_int4():
     # the paper's capacity setting (Section 3.4: 3.3 million tokens with a 4-bit KV cache) at its shape
     _long_context_stack(3300000, duo.DUO_KV_INT4, 32, check_layers=(9,), seed=6)
+
+
+@pytest.mark.parametrize("hq,hkv,block", [(32, 8, 128), (32, 32, 0)])
+def test_gate_mixed_forward_at_training_length(hq, hkv, block):
+    # the identification-phase forward at the longest training length of the appendix (32000 tokens),
+    # sink 128 / recent 256 as in Section 3.1; sampled rows of the whole-sequence output
+    import torch
+    d, n, sink, recent, seed = 128, 32000, 128, 256, 8
+    table = device_table()
+    q = device_fill(table, seed, 0, synth.TENSOR_Q, 1, 0, n, hq, d)
+    k = device_fill(table, seed, 0, synth.TENSOR_K, 1, 0, n, hkv, d)
+    v = device_fill(table, seed, 0, synth.TENSOR_V, 1, 0, n, hkv, d)
+    alpha = np.random.default_rng(seed).uniform(0, 1, hkv).astype(np.float32)
+    alpha[0], alpha[-1] = 1.0, 0.0
+    handle = duo.duo_cache_create(1, 1, hq, hkv, d, sink, recent, 64, np.ones((1, hkv), dtype=np.uint8))
+    try:
+        out, ws = torch.empty_like(q), torch.empty_like(q)
+        duo.duo_attn_gate_mixed(handle, 0, q, k, v, n, alpha, out, ws, block=block)
+        torch.cuda.synchronize()
+        got = from_dev_bits(out)[0]
+    finally:
+        duo.duo_cache_destroy(handle)
+    rng = np.random.default_rng(seed + 1)
+    positions = sorted(set([0, 1, sink - 1, sink, sink + recent - 1, sink + recent, 255, 256, n - 1]
+                           + rng.integers(0, n, size=12).tolist()))
+    k_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_K, 0, n, hkv, d))
+    v_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_V, 0, n, hkv, d))
+    q_rows = np.stack([synth.counter_bf16(seed, 0, synth.TENSOR_Q, 0, p, 1, hq, d)[0] for p in positions])
+    want = oracle.gate_mixed_rows(synth.bf16_bits_to_f64(q_rows), k_hist, v_hist, alpha, positions, sink, recent,
+                                  block=block)
+    assert_close(synth.bf16_bits_to_f64(got[positions]), want, "gate-mixed rows at 32000 tokens")
