@@ -30,6 +30,8 @@ from .fp8_codec import (  # noqa: F401
 )
 from .int4_codec import (  # noqa: F401
     quantize_rows_int4,
+    quantize_rows_int8,
+    dequantize_rows_int8,
     dequantize_rows_int4,
     pack_int4,
     unpack_int4,

@@ -12,31 +12,46 @@ respect to the paper.  The codec built here is the usual asymmetric per-row one:
 
 Codes are packed two per byte, element 2i in the low nibble and element 2i + 1 in the high one.
 
-Pins (tests/test_oracle_int4.py): hand-computed rows, extremes map to 0 and 15, ties go to the even
-code, constant rows, error bound scale / 2, packing layout.
+The 8-bit form of the same codec (codes 0..255, scale = (hi - lo) / 255, one code per byte) is
+quantize_rows_int8 / dequantize_rows_int8.
+
+Pins (tests/test_oracle_int4.py): hand-computed rows, extremes map to 0 and 15 (255), ties go to the
+even code, constant rows, error bound scale / 2, packing layout.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
-def quantize_rows_int4(x):
-    """x [..., D] (fp32-representable) -> (codes uint8 [..., D] in 0..15, scale fp32 [...], lo fp32 [...])."""
+def _quantize_rows(x, top):
     x = np.asarray(x, dtype=np.float32)
     lo = np.min(x, axis=-1).astype(np.float32)
     hi = np.max(x, axis=-1).astype(np.float32)
     span = (hi - lo).astype(np.float32)
-    scale = np.where(span == 0, np.float32(1.0), span / np.float32(15.0)).astype(np.float32)
+    scale = np.where(span == 0, np.float32(1.0), span / np.float32(top)).astype(np.float32)
     t = (x - lo[..., None]).astype(np.float32)
     r = (t / scale[..., None]).astype(np.float32)
-    code = np.clip(np.rint(r), 0, 15).astype(np.uint8)      # numpy rint rounds half to even
+    code = np.clip(np.rint(r), 0, top).astype(np.uint8)     # numpy rint rounds half to even
     return code, scale, lo
+
+
+def quantize_rows_int4(x):
+    """x [..., D] (fp32-representable) -> (codes uint8 [..., D] in 0..15, scale fp32 [...], lo fp32 [...])."""
+    return _quantize_rows(x, 15)
+
+
+def quantize_rows_int8(x):
+    """The 8-bit form: codes 0..255, scale = (hi - lo) / 255."""
+    return _quantize_rows(x, 255)
 
 
 def dequantize_rows_int4(codes, scale, lo) -> np.ndarray:
     """float64 values code * scale + lo."""
     return (np.asarray(codes, dtype=np.float64) * np.asarray(scale, dtype=np.float64)[..., None]
             + np.asarray(lo, dtype=np.float64)[..., None])
+
+
+dequantize_rows_int8 = dequantize_rows_int4     # the same expression: code * scale + lo
 
 
 def pack_int4(codes) -> np.ndarray:
