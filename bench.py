@@ -224,7 +224,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- algorithmic work
-    row_bytes = {0: 2 * d, 1: d + 4, 2: d // 2 + 8}[kv_dtype]
+    row_bytes = {0: 2 * d, 1: d + 4, 2: d // 2 + 8, 3: d + 8}[kv_dtype]
     n_timed_tokens = n_decode if attn_prefill else n_decode * args.steps
     dec_bytes = []           # per launch (one layer, one token, all sequences)
     for t in range(n_timed_tokens):
@@ -275,7 +275,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": False if n_decode else True, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "bf16", 1: "bf16 (fp8 e4m3 KV, fp32 accumulate)",
-                  2: "bf16 (int4 KV, fp32 accumulate)"}[kv_dtype], "data": "synthetic",
+                  2: "bf16 (int4 KV, fp32 accumulate)", 3: "bf16 (int8 KV, fp32 accumulate)"}[kv_dtype], "data": "synthetic",
         "config": {"workload": w["desc"], "name": args.workload, "n_layers": n_layers, "n_q_heads": hq,
                    "n_kv_heads": hkv, "head_dim": d, "retrieval_kv_heads": n_ret, "sink": sink, "recent": recent,
                    "batch": B, "prefill_tokens": n_prefill, "chunk": chunk, "decode_steps": n_decode,
@@ -442,6 +442,8 @@ def cpu_baseline(synth, seed, w, mask, n_ctx, batch):
             x = synth.bf16_bits_to_f32(out[p0:p0 + qstep])
             if kv_dtype == 2:
                 deq[p0:p0 + qstep] = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(x))
+            elif kv_dtype == 3:
+                deq[p0:p0 + qstep] = oracle.dequantize_rows_int8(*oracle.quantize_rows_int8(x))
             else:
                 codes, scales = oracle.quantize_rows(x)
                 deq[p0:p0 + qstep] = oracle.dequantize_rows(codes, scales)

@@ -57,11 +57,13 @@ typedef enum {
                          code = RNE-saturating(x / scale), x_hat = value(code) * scale.
                          This stands in for the paper's 4-bit KV setting (Section 3.4,
                          combination with quantization). */
-  DUO_KV_INT4 = 2     /* caches hold 4-bit codes, two per byte (element 2i in the low nibble), + two fp32
+  DUO_KV_INT4 = 2,    /* caches hold 4-bit codes, two per byte (element 2i in the low nibble), + two fp32
                          per (token, KV head), K and V separately: (scale, lo) with lo = min x,
                          scale = (max x - lo) / 15 (1 for a constant row), code = clamp(round-to-nearest-
                          even((x - lo) / scale), 0, 15) in fp32, x_hat = code * scale + lo.  The paper's own
                          capacity setting is a 4-bit KV cache (Section 3.4) whose codec it does not give. */
+  DUO_KV_INT8 = 3     /* the 8-bit form of the same asymmetric codec: one code 0..255 per byte,
+                         scale = (max x - lo) / 255, the same (scale, lo) fp32 pair per row */
 } duo_kv_dtype_t;
 
 typedef struct {
@@ -173,8 +175,8 @@ int duo_decode_step(duo_cache_t* cache, int layer, const void* q, const void* k,
 /* Test hook: the tokens one (layer, sequence, KV head) cache currently holds, in
  * ascending position order.  k_out/v_out: device buffers of capacity
  * `capacity` rows, each row head_dim bf16 (DUO_KV_BF16) or head_dim bytes
- * (DUO_KV_FP8_E4M3) or head_dim / 2 bytes (DUO_KV_INT4); kscale_out/vscale_out: fp32 [capacity]
- * (fp8) or fp32 [capacity][2] = (scale, lo) pairs (int4), NULL allowed for bf16; positions_out: device int64 [capacity].  *count_out (HOST)
+ * (DUO_KV_FP8_E4M3, DUO_KV_INT8) or head_dim / 2 bytes (DUO_KV_INT4); kscale_out/vscale_out: fp32
+ * [capacity] (fp8) or fp32 [capacity][2] = (scale, lo) pairs (int4, int8), NULL allowed for bf16; positions_out: device int64 [capacity].  *count_out (HOST)
  * receives the number of rows.  DUO_ERANGE if capacity is too small. */
 int duo_cache_export(duo_cache_t* cache, int layer, int batch_idx, int kv_head,
                      void* k_out, void* v_out, float* kscale_out, float* vscale_out,

@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("DUOATTN_LIB") or os.path.join(_HERE, "libduoattn.so")
 SYNTH_LIB_PATH = os.path.join(_HERE, "libduosynth.so")
 
 DUO_OK, DUO_EINVAL, DUO_ENOMEM, DUO_ERANGE, DUO_ESTATE, DUO_EHIP = 0, -1, -2, -3, -4, -5
-DUO_KV_BF16, DUO_KV_FP8_E4M3, DUO_KV_INT4 = 0, 1, 2
+DUO_KV_BF16, DUO_KV_FP8_E4M3, DUO_KV_INT4, DUO_KV_INT8 = 0, 1, 2, 3
 
 
 class DuoError(RuntimeError):

@@ -163,7 +163,8 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   if (cfg->max_seq < 1) return fail(DUO_EINVAL, "max_seq must be >= 1 (got %lld)", (long long)cfg->max_seq);
   if (cfg->max_seq > ((int64_t)1 << 31) - 1024)
     return fail(DUO_EINVAL, "max_seq %lld exceeds the supported 2^31 - 1024", (long long)cfg->max_seq);
-  if (cfg->kv_dtype != DUO_KV_BF16 && cfg->kv_dtype != DUO_KV_FP8_E4M3 && cfg->kv_dtype != DUO_KV_INT4)
+  if (cfg->kv_dtype != DUO_KV_BF16 && cfg->kv_dtype != DUO_KV_FP8_E4M3 && cfg->kv_dtype != DUO_KV_INT4 &&
+      cfg->kv_dtype != DUO_KV_INT8)
     return fail(DUO_EINVAL, "kv_dtype %d unknown", cfg->kv_dtype);
   if (!cfg->retrieval_mask) return fail(DUO_EINVAL, "retrieval_mask must not be NULL");
   if (!(cfg->softmax_scale >= 0.0f) || std::isinf(cfg->softmax_scale))
@@ -175,9 +176,10 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   c->cfg.retrieval_mask = nullptr;
   c->layers.resize(cfg->n_layers);
 
-  const int sc_per_row = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? 1 : (cfg->kv_dtype == DUO_KV_INT4 ? 2 : 0);
+  const int sc_per_row = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? 1
+                         : (cfg->kv_dtype == DUO_KV_INT4 || cfg->kv_dtype == DUO_KV_INT8 ? 2 : 0);
   const bool quantised = sc_per_row > 0;   // scale arrays are allocated
-  const int row_bytes = cfg->kv_dtype == DUO_KV_FP8_E4M3 ? cfg->head_dim
+  const int row_bytes = cfg->kv_dtype == DUO_KV_FP8_E4M3 || cfg->kv_dtype == DUO_KV_INT8 ? cfg->head_dim
                         : (cfg->kv_dtype == DUO_KV_INT4 ? cfg->head_dim / 2 : cfg->head_dim * 2);
   const int64_t str_rows = (int64_t)cfg->sink + cfg->recent;
   const float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);

@@ -40,8 +40,8 @@ struct LayerView {
   int32_t n_ret, n_str;
   int32_t batch, n_q_heads, n_kv_heads, group, head_dim;
   int32_t sink, recent;
-  int32_t row_bytes;          // head_dim * 2 (bf16), head_dim (fp8) or head_dim / 2 (int4)
-  int32_t kv_mode;            // duo_kv_dtype_t: 0 bf16, 1 fp8 codes + one scale per row, 2 int4 codes + (scale, minimum) per row
+  int32_t row_bytes;          // head_dim * 2 (bf16), head_dim (fp8, int8) or head_dim / 2 (int4)
+  int32_t kv_mode;            // duo_kv_dtype_t: 0 bf16, 1 fp8 codes + one scale per row, 2 int4 / 3 int8 codes + (scale, minimum) per row
   int32_t sc_per_row;         // floats per row in the scale arrays: 0, 1 or 2
   int64_t max_seq;
   float scale;                // softmax scale

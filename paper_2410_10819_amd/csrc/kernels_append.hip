@@ -35,7 +35,7 @@ __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0
 
 // One 16-byte chunk (8 bf16 values) of one row per thread; the head_dim/8 threads
 // of a row sit in adjacent lanes.
-// MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 codes + (scale, minimum).
+// MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 / 3 int8 codes + (scale, minimum).
 template <int D, int MODE>
 __global__ __launch_bounds__(256) void append_kernel(LayerView lv, const uint4* __restrict__ k_in,
                                                      const uint4* __restrict__ v_in, int64_t pos0,
@@ -80,10 +80,12 @@ __global__ __launch_bounds__(256) void append_kernel(LayerView lv, const uint4* 
       kd[dst_row * LPR + sub] = kc;
       vd[dst_row * LPR + sub] = vc;
     }
-  } else if constexpr (MODE == 2) {
-    // asymmetric 4-bit codes per row, all in fp32: lo = min, scale = (max - lo) / 15 (1 for a
-    // constant row), code = clamp(rint((x - lo) / scale), 0, 15); element j of the lane's eight
-    // goes to bits 4 j of its dword, so element 2 i sits in the low nibble of byte i of the row
+  } else if constexpr (MODE == 2 || MODE == 3) {
+    // asymmetric codes per row, all in fp32: lo = min, scale = (max - lo) / top (1 for a constant
+    // row), code = clamp(rint((x - lo) / scale), 0, top), top = 15 or 255.  4-bit: element j of the
+    // lane's eight goes to bits 4 j of its dword, so element 2 i sits in the low nibble of byte i
+    // of the row; 8-bit: one byte per element.
+    constexpr float kTop = MODE == 2 ? 15.0f : 255.0f;
     const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
     const uint32_t vw[4] = {vc.x, vc.y, vc.z, vc.w};
     float kf[8], vf[8];
@@ -104,21 +106,29 @@ __global__ __launch_bounds__(256) void append_kernel(LayerView lv, const uint4* 
       vmin = fminf(vmin, __shfl_xor(vmin, off)); vmax = fmaxf(vmax, __shfl_xor(vmax, off));
     }
     const float kspan = kmax - kmin, vspan = vmax - vmin;
-    const float ks = kspan == 0.f ? 1.0f : kspan / 15.0f;
-    const float vs = vspan == 0.f ? 1.0f : vspan / 15.0f;
-    uint32_t kq = 0, vq = 0;
+    const float ks = kspan == 0.f ? 1.0f : kspan / kTop;
+    const float vs = vspan == 0.f ? 1.0f : vspan / kTop;
+    constexpr int kBits = MODE == 2 ? 4 : 8;
+    uint32_t kq[2] = {0, 0}, vq[2] = {0, 0};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float kr = fminf(fmaxf(rintf((kf[i] - kmin) / ks), 0.f), 15.f);
-      const float vr = fminf(fmaxf(rintf((vf[i] - vmin) / vs), 0.f), 15.f);
-      kq |= (uint32_t)kr << (4 * i);
-      vq |= (uint32_t)vr << (4 * i);
+      const float kr = fminf(fmaxf(rintf((kf[i] - kmin) / ks), 0.f), kTop);
+      const float vr = fminf(fmaxf(rintf((vf[i] - vmin) / vs), 0.f), kTop);
+      kq[i * kBits / 32] |= (uint32_t)kr << (i * kBits % 32);
+      vq[i * kBits / 32] |= (uint32_t)vr << (i * kBits % 32);
     }
     if (write) {
-      uint32_t* kd = (uint32_t*)(retrieval ? lv.k_ret : lv.k_str);
-      uint32_t* vd = (uint32_t*)(retrieval ? lv.v_ret : lv.v_str);
-      kd[dst_row * LPR + sub] = kq;
-      vd[dst_row * LPR + sub] = vq;
+      if constexpr (MODE == 2) {
+        uint32_t* kd = (uint32_t*)(retrieval ? lv.k_ret : lv.k_str);
+        uint32_t* vd = (uint32_t*)(retrieval ? lv.v_ret : lv.v_str);
+        kd[dst_row * LPR + sub] = kq[0];
+        vd[dst_row * LPR + sub] = vq[0];
+      } else {
+        uint2* kd = (uint2*)(retrieval ? lv.k_ret : lv.k_str);
+        uint2* vd = (uint2*)(retrieval ? lv.v_ret : lv.v_str);
+        kd[dst_row * LPR + sub] = make_uint2(kq[0], kq[1]);
+        vd[dst_row * LPR + sub] = make_uint2(vq[0], vq[1]);
+      }
       if (sub == 0) {
         ((float2*)(retrieval ? lv.ks_ret : lv.ks_str))[dst_row] = make_float2(ks, kmin);
         ((float2*)(retrieval ? lv.vs_ret : lv.vs_str))[dst_row] = make_float2(vs, vmin);
@@ -217,13 +227,15 @@ hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int6
   const uint4* kk = (const uint4*)k;
   const uint4* vv = (const uint4*)v;
 #define DUO_APPEND(D_, M_) append_kernel<D_, M_><<<grid, block, 0, stream>>>(lv, kk, vv, pos0, n_new, total_rows)
-  if (lv.kv_mode < 0 || lv.kv_mode > 2) return hipErrorInvalidValue;
+  if (lv.kv_mode < 0 || lv.kv_mode > 3) return hipErrorInvalidValue;
   if (lv.head_dim == 128) {
-    if (lv.kv_mode == 2) DUO_APPEND(128, 2);
+    if (lv.kv_mode == 3) DUO_APPEND(128, 3);
+    else if (lv.kv_mode == 2) DUO_APPEND(128, 2);
     else if (lv.kv_mode == 1) DUO_APPEND(128, 1);
     else DUO_APPEND(128, 0);
   } else {
-    if (lv.kv_mode == 2) DUO_APPEND(64, 2);
+    if (lv.kv_mode == 3) DUO_APPEND(64, 3);
+    else if (lv.kv_mode == 2) DUO_APPEND(64, 2);
     else if (lv.kv_mode == 1) DUO_APPEND(64, 1);
     else DUO_APPEND(64, 0);
   }

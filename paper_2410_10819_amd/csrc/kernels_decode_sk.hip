@@ -40,6 +40,8 @@
 //     to match, so no instruction is spent on order.  V rows are staged in LDS as
 //     codes and come back through the 4-bit transposing read, sixteen d by sixteen
 //     (key, row block) pairs per lane group and read.
+//   - int8 caches: the same algebra with the codes 0 .. 255 themselves as bf16
+//     operands (exact), widened like the fp8 codes, and 127.5 as the midpoint.
 #include "duo_internal.h"
 
 #include <type_traits>
@@ -121,19 +123,30 @@ __device__ inline uint4 int4x8_to_bf16x8(uint32_t w) {
   return r;
 }
 
-// MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 codes + (scale, lo).
+// Four 8-bit codes (one dword) -> four bf16 values 0 .. 255 (two dwords); exact: an integer below
+// 256 has at most 8 significant bits, so the upper half of its float is the bf16 value.
+__device__ inline uint2 u8x4_to_bf16x4(uint32_t w) {
+  const float f0 = (float)(w & 0xFFu), f1 = (float)((w >> 8) & 0xFFu);
+  const float f2 = (float)((w >> 16) & 0xFFu), f3 = (float)(w >> 24);
+  uint2 r;
+  r.x = __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
+  r.y = __builtin_amdgcn_perm(__float_as_uint(f3), __float_as_uint(f2), 0x07060302u);
+  return r;
+}
+
+// MODE: 0 bf16 rows, 1 fp8 codes + scale, 2 int4 / 3 int8 codes + (scale, lo).
 template <int D, int MODE>
 struct Shape {
   static constexpr int NKK = D / 32;                 // matrix-core k-steps of K Q^T
   static constexpr int NMB = D / 16;                 // 16-row blocks of O^T
   static constexpr int LROW = D * 2;                 // bytes of a (bf16) V row in LDS
   static constexpr int CPR = D / 8;                  // 16-byte pieces per LDS row
-  static constexpr int GROW = MODE == 2 ? D / 2 : (MODE == 1 ? D : D * 2);   // bytes of a row in the cache
+  static constexpr int GROW = MODE == 2 ? D / 2 : (MODE == 0 ? D * 2 : D);   // bytes of a row in the cache
   static constexpr int VPR = GROW / 16;              // 16-byte pieces per cache row
   static constexpr int VRPI = 64 / VPR;              // V rows covered by one wavefront load
   static constexpr int NV = kUnit / VRPI;            // V loads per lane and block
-  static constexpr int KB = MODE == 2 ? 4 : (MODE == 1 ? 8 : 16);   // bytes of K per lane, 16-key group and k-step
-  static constexpr int NSC = MODE == 2 ? 2 : 1;      // floats per row in the scale arrays
+  static constexpr int KB = MODE == 2 ? 4 : (MODE == 0 ? 16 : 8);   // bytes of K per lane, 16-key group and k-step
+  static constexpr int NSC = MODE >= 2 ? 2 : 1;      // floats per row in the scale arrays
   __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
   // int4: V rows are staged as codes (GROW bytes a row); 16-byte pieces swizzled so that the rows one
   // transposing read touches (keys 4 qd + r and 16 + 4 qd + r) spread over the banks
@@ -162,7 +175,12 @@ struct KeyParams {
 template <int D, int MODE>
 __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_sk_kernel(DecodeArgs a) {
   using S = Shape<D, MODE>;
-  constexpr bool FP8 = MODE == 1, INT4 = MODE == 2, QUANT = MODE != 0;
+  constexpr bool FP8 = MODE == 1, INT4 = MODE == 2, INT8 = MODE == 3, QUANT = MODE != 0;
+  constexpr bool ASYM = INT4 || INT8;    // integer codes with (scale, lo) per row
+  constexpr bool BYTES = FP8 || INT8;    // one byte per element
+  // the matrix-core operands of integer codes are kOff + code (128 + nibble by the OR trick, the
+  // byte itself); kMid is the middle of the code range
+  constexpr float kOff = INT4 ? 128.f : 0.f, kMid = INT4 ? 7.5f : 127.5f;
   constexpr int NKK = S::NKK, NMB = S::NMB, LROW = S::LROW, GROW = S::GROW;
   const LayerView& lv = a.lv;
   const int G = lv.group;
@@ -246,23 +264,25 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
     // ---- query operand: lane (hd, qd) holds q[head hd][32 kk + 8 qd .. + 7]; for an int4 cache,
     // whose lanes load D/4 consecutive codes of a key, q[head hd][(D/4) qd + 8 kk + sigma(0..7)]
     bf16x8 qf[NKK];
-    float qsum = 0.f;   // int4: sum_d q[head hd][d]
+    float qsum = 0.f;   // integer codes: sum_d q[head hd][d]
     {
       const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G + (head_ok ? hd : 0)) * D;
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
         uint4 raw = *(const uint4*)(qrow + (INT4 ? (D / 4) * qd + 8 * kk : 32 * kk + 8 * qd));
         if (!head_ok) raw = make_uint4(0, 0, 0, 0);
-        if constexpr (INT4) {
+        if constexpr (ASYM) {
           const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) qsum += __uint_as_float(w[i] << 16) + __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+        if constexpr (INT4) {
           raw = make_uint4(__builtin_amdgcn_perm(raw.z, raw.x, 0x05040100u), __builtin_amdgcn_perm(raw.z, raw.x, 0x07060302u),
                            __builtin_amdgcn_perm(raw.w, raw.y, 0x05040100u), __builtin_amdgcn_perm(raw.w, raw.y, 0x07060302u));
         }
         qf[kk] = __builtin_bit_cast(bf16x8, raw);
       }
-      if constexpr (INT4) {
+      if constexpr (ASYM) {
         qsum += __shfl_xor(qsum, 16);
         qsum += __shfl_xor(qsum, 32);
       }
@@ -306,7 +326,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           const uint8_t* p = kb + (k_off + (uint32_t)(16 * t * GROW + 4 * kk * S::KB));
-          if constexpr (FP8) {
+          if constexpr (BYTES) {
             const uint2 x = *(const uint2*)p;
             rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y;
           } else {
@@ -318,7 +338,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
 #pragma unroll
       for (int j = 0; j < S::NV; ++j) rb.v[j] = *(const uint4*)(vb + (v_off + (uint32_t)(j * 1024)));
       if constexpr (FP8) rb.sc[0] = (lane < 32 ? ksbase : vsbase)[r0 + (lane & 31)];
-      if constexpr (INT4) {
+      if constexpr (ASYM) {
         const float2 x = ((const float2*)(lane < 32 ? ksbase : vsbase))[r0 + (lane & 31)];
         rb.sc[0] = x.x; rb.sc[1] = x.y;
       }
@@ -336,7 +356,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           if constexpr (INT4) {
-          } else if constexpr (FP8) {
+          } else if constexpr (BYTES) {
             const uint2 x = *(const uint2*)(kr + (qd + 4 * kk) * 8);
             rb.k[t][kk][0] = x.x; rb.k[t][kk][1] = x.y;
           } else {
@@ -354,7 +374,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
       if constexpr (QUANT) {
         int64_t r = r0 + (lane & 31);
         r = r < n_rows ? r : last_row;
-        if constexpr (INT4) {
+        if constexpr (ASYM) {
           const float2 x = ((const float2*)(lane < 32 ? ksbase : vsbase))[r];
           rb.sc[0] = x.x; rb.sc[1] = x.y;
         } else {
@@ -368,7 +388,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         // int4 operands are 128 + code: start from -128 sum(q), so the result is sum(q code)
-        const float s0 = INT4 ? -128.f * qsum : 0.f;
+        const float s0 = -kOff * qsum;
         sacc[t] = (f32x4){s0, s0, s0, s0};
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
@@ -387,7 +407,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           float s;
-          if constexpr (INT4) {
+          if constexpr (ASYM) {
             s = sacc[t][r] * kp.ks[4 * t + r] + kp.klo[4 * t + r] * qsum;
           } else if constexpr (FP8) {
             s = sacc[t][r] * kp.ks[4 * t + r];
@@ -409,7 +429,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
         const float mu = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = fast_exp2(m_ref - mu);
         l_lane *= alpha;
-        if constexpr (INT4) { corr_lane *= alpha; pb_sum *= alpha; }
+        if constexpr (ASYM) { corr_lane *= alpha; pb_sum *= alpha; }
 #pragma unroll
         for (int mb = 0; mb < NMB; ++mb) oacc[mb] *= alpha;
         m_ref = m_new;
@@ -427,9 +447,9 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
         const int src = INT4 ? (i >> 1) + 4 * (i & 1) : i;
         pb[i] = (__bf16)(QUANT ? p[src] * kp.vs[src] : p[src]);
       }
-      if constexpr (INT4) {
-        // the matrix core sums pb * (128 + code) = pb * (code - 7.5) + 135.5 pb: the second term is
-        // taken back at the end exactly as rounded; kp.vlo holds lo + 7.5 scale
+      if constexpr (ASYM) {
+        // the matrix core sums pb * (kOff + code) = pb * (code - kMid) + (kOff + kMid) pb: the second
+        // term is taken back at the end exactly as rounded; kp.vlo holds lo + kMid scale
 #pragma unroll
         for (int i = 0; i < 8; ++i) corr_lane += p[i] * kp.vlo[i];
         const uint32_t one2 = 0x3F803F80u;
@@ -474,15 +494,17 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
     // Convert / stage the raw registers of a block (V rows into the wavefront's LDS buffer, 16-byte
     // pieces swizzled by row; fp8 scales through LDS into key order) and start its arithmetic.
     // After this the raw registers are free for the next block's loads.
+    // four one-byte codes -> four bf16 values
+    auto widen4 = [&](uint32_t w) { return INT8 ? u8x4_to_bf16x4(w) : e4m3x4_to_bf16x4(w); };
     auto stage_qk = [&](const Raw& rb, f32x4 (&sacc)[2], KeyParams& kp) {
 #pragma unroll
       for (int j = 0; j < S::NV; ++j) {
         const int row = j * S::VRPI + lane / S::VPR, pc = lane % S::VPR;
         if constexpr (INT4) {
           *(uint4*)(my_v + row * GROW + ((pc ^ S::c_swz(row)) * 16)) = rb.v[j];   // codes as they are
-        } else if constexpr (FP8) {
-          const uint2 a0 = e4m3x4_to_bf16x4(rb.v[j].x), a1 = e4m3x4_to_bf16x4(rb.v[j].y);
-          const uint2 a2 = e4m3x4_to_bf16x4(rb.v[j].z), a3 = e4m3x4_to_bf16x4(rb.v[j].w);
+        } else if constexpr (BYTES) {
+          const uint2 a0 = widen4(rb.v[j].x), a1 = widen4(rb.v[j].y);
+          const uint2 a2 = widen4(rb.v[j].z), a3 = widen4(rb.v[j].w);
           *(uint4*)(my_v + row * LROW + (((2 * pc) ^ S::v_swz(row)) * 16)) = make_uint4(a0.x, a0.y, a1.x, a1.y);
           *(uint4*)(my_v + row * LROW + (((2 * pc + 1) ^ S::v_swz(row)) * 16)) = make_uint4(a2.x, a2.y, a3.x, a3.y);
         } else {
@@ -496,20 +518,20 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
         for (int kk = 0; kk < NKK; ++kk) {
           if constexpr (INT4) {
             kf[t][kk] = __builtin_bit_cast(bf16x8, int4x8_to_bf16x8(rb.k[t][kk][0]));
-          } else if constexpr (FP8) {
-            const uint2 x0 = e4m3x4_to_bf16x4(rb.k[t][kk][0]), x1 = e4m3x4_to_bf16x4(rb.k[t][kk][1]);
+          } else if constexpr (BYTES) {
+            const uint2 x0 = widen4(rb.k[t][kk][0]), x1 = widen4(rb.k[t][kk][1]);
             kf[t][kk] = __builtin_bit_cast(bf16x8, make_uint4(x0.x, x0.y, x1.x, x1.y));
           } else {
             kf[t][kk] = __builtin_bit_cast(bf16x8, make_uint4(rb.k[t][kk][0], rb.k[t][kk][1], rb.k[t][kk][2], rb.k[t][kk][3]));
           }
         }
       qk(kf, sacc);
-      if constexpr (INT4) {
+      if constexpr (ASYM) {
         // [0..31] K scale, [32..63] K lo, [64..95] V scale, [96..127] V lo, each in row order
         // the lane that loaded a row's parameters folds the constants in before sharing them
         const int at = lane < 32 ? lane : lane + 32;
         sm_sc[wave][at] = lane < 32 ? rb.sc[0] * c_scale : rb.sc[0];
-        sm_sc[wave][at + 32] = lane < 32 ? rb.sc[1] * c_scale : rb.sc[1] + 7.5f * rb.sc[0];
+        sm_sc[wave][at + 32] = lane < 32 ? rb.sc[1] * c_scale : rb.sc[1] + kMid * rb.sc[0];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const float4 s4 = *(const float4*)&sm_sc[wave][16 * t + 4 * qd];
@@ -592,8 +614,10 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
       uint4 kc = make_uint4(0, 0, 0, 0), vc = kc;
       if (row_lane) { kc = *(const uint4*)(kin + 8 * lane); vc = *(const uint4*)(vin + 8 * lane); }
       float ks1 = 1.f, vs1 = 1.f, klo1 = 0.f, vlo1 = 0.f;
-      if constexpr (INT4) {
+      if constexpr (ASYM) {
         // quantise exactly as the append kernel does, then attend to the codes like a cached row
+        constexpr float kTop = INT4 ? 15.0f : 255.0f;
+        constexpr int kBits = INT4 ? 4 : 8;
         const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w}, vw[4] = {vc.x, vc.y, vc.z, vc.w};
         float kf4[8], vf4[8];
 #pragma unroll
@@ -614,24 +638,36 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
           vmin = fminf(vmin, __shfl_xor(vmin, off)); vmax = fmaxf(vmax, __shfl_xor(vmax, off));
         }
         const float kspan = kmax - kmin, vspan = vmax - vmin;
-        ks1 = kspan == 0.f ? 1.0f : kspan / 15.0f;
-        vs1 = vspan == 0.f ? 1.0f : vspan / 15.0f;
-        uint32_t kq = 0, vq = 0;
+        ks1 = kspan == 0.f ? 1.0f : kspan / kTop;
+        vs1 = vspan == 0.f ? 1.0f : vspan / kTop;
+        uint32_t kq[2] = {0, 0}, vq[2] = {0, 0};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          kq |= (uint32_t)fminf(fmaxf(rintf((kf4[i] - kmin) / ks1), 0.f), 15.f) << (4 * i);
-          vq |= (uint32_t)fminf(fmaxf(rintf((vf4[i] - vmin) / vs1), 0.f), 15.f) << (4 * i);
+          kq[i * kBits / 32] |= (uint32_t)fminf(fmaxf(rintf((kf4[i] - kmin) / ks1), 0.f), kTop) << (i * kBits % 32);
+          vq[i * kBits / 32] |= (uint32_t)fminf(fmaxf(rintf((vf4[i] - vmin) / vs1), 0.f), kTop) << (i * kBits % 32);
         }
         if (a.commit && row_lane) {
-          *(uint32_t*)(kbase + new_row * GROW + lane * 4) = kq;
-          *(uint32_t*)(vbase + new_row * GROW + lane * 4) = vq;
+          if constexpr (INT4) {
+            *(uint32_t*)(kbase + new_row * GROW + lane * 4) = kq[0];
+            *(uint32_t*)(vbase + new_row * GROW + lane * 4) = vq[0];
+          } else {
+            *(uint2*)(kbase + new_row * GROW + lane * 8) = make_uint2(kq[0], kq[1]);
+            *(uint2*)(vbase + new_row * GROW + lane * 8) = make_uint2(vq[0], vq[1]);
+          }
           if (lane == 0) {
             ((float2*)ksbase)[new_row] = make_float2(ks1, kmin);
             ((float2*)vsbase)[new_row] = make_float2(vs1, vmin);
           }
         }
-        kc = int4x8_to_bf16x8(kq);
-        vc.x = vq;   // V goes to the staging buffer as codes
+        if constexpr (INT4) {
+          kc = int4x8_to_bf16x8(kq[0]);
+          vc.x = vq[0];   // V goes to the staging buffer as codes
+        } else {
+          const uint2 k0 = u8x4_to_bf16x4(kq[0]), k1 = u8x4_to_bf16x4(kq[1]);
+          const uint2 v0 = u8x4_to_bf16x4(vq[0]), v1 = u8x4_to_bf16x4(vq[1]);
+          kc = make_uint4(k0.x, k0.y, k1.x, k1.y);
+          vc = make_uint4(v0.x, v0.y, v1.x, v1.y);
+        }
         ks1 = __shfl(ks1, 0); vs1 = __shfl(vs1, 0);
         klo1 = __shfl(kmin, 0); vlo1 = __shfl(vmin, 0);
       } else if constexpr (!FP8) {
@@ -704,7 +740,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
       }
       KeyParams kp;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { kp.ks[i] = ks1 * c_scale; kp.vs[i] = vs1; kp.klo[i] = klo1 * c_scale; kp.vlo[i] = vlo1 + 7.5f * vs1; }
+      for (int i = 0; i < 8; ++i) { kp.ks[i] = ks1 * c_scale; kp.vs[i] = vs1; kp.klo[i] = klo1 * c_scale; kp.vlo[i] = vlo1 + kMid * vs1; }
       const int64_t saved = exclude;
       exclude = -1;
       f32x4 sacc[2];
@@ -717,10 +753,10 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
     float l_head = l_lane + __shfl_xor(l_lane, 16);
     l_head += __shfl_xor(l_head, 32);
     float corr_head = 0.f;
-    if constexpr (INT4) {
+    if constexpr (ASYM) {
       corr_head = corr_lane + __shfl_xor(corr_lane, 16);
       corr_head += __shfl_xor(corr_head, 32);
-      corr_head -= 135.5f * pb_sum[0];
+      corr_head -= (kOff + kMid) * pb_sum[0];
     }
     __syncthreads();   // every wavefront is done with its V staging buffer
     if (head_ok) {
@@ -849,13 +885,15 @@ hipError_t launch_decode_sk(const DecodeArgs& a, hipStream_t stream) {
       (ret_units > 0 && a.ret_workers < 1) || a.units_ret < 1 || a.units_str < 1)
     return hipErrorInvalidValue;
   dim3 grid((unsigned)(a.ret_workers + lv.batch * lv.n_str));
-  if (lv.kv_mode < 0 || lv.kv_mode > 2) return hipErrorInvalidValue;
+  if (lv.kv_mode < 0 || lv.kv_mode > 3) return hipErrorInvalidValue;
   if (lv.head_dim == 128) {
-    if (lv.kv_mode == 2) decode_sk_kernel<128, 2><<<grid, 256, 0, stream>>>(a);
+    if (lv.kv_mode == 3) decode_sk_kernel<128, 3><<<grid, 256, 0, stream>>>(a);
+    else if (lv.kv_mode == 2) decode_sk_kernel<128, 2><<<grid, 256, 0, stream>>>(a);
     else if (lv.kv_mode == 1) decode_sk_kernel<128, 1><<<grid, 256, 0, stream>>>(a);
     else decode_sk_kernel<128, 0><<<grid, 256, 0, stream>>>(a);
   } else {
-    if (lv.kv_mode == 2) decode_sk_kernel<64, 2><<<grid, 256, 0, stream>>>(a);
+    if (lv.kv_mode == 3) decode_sk_kernel<64, 3><<<grid, 256, 0, stream>>>(a);
+    else if (lv.kv_mode == 2) decode_sk_kernel<64, 2><<<grid, 256, 0, stream>>>(a);
     else if (lv.kv_mode == 1) decode_sk_kernel<64, 1><<<grid, 256, 0, stream>>>(a);
     else decode_sk_kernel<64, 0><<<grid, 256, 0, stream>>>(a);
   }

@@ -60,6 +60,9 @@ def oracle_kv(k_bits, v_bits, kv_dtype):
     elif kv_dtype == 2:
         k = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(k.astype(np.float32)))
         v = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(v.astype(np.float32)))
+    elif kv_dtype == 3:
+        k = oracle.dequantize_rows_int8(*oracle.quantize_rows_int8(k.astype(np.float32)))
+        v = oracle.dequantize_rows_int8(*oracle.quantize_rows_int8(v.astype(np.float32)))
     return k, v
 
 
@@ -181,6 +184,8 @@ def oracle_history_f64(bits, kv_dtype, workers=8):
         x = synth.bf16_bits_to_f32(bits[p0:p0 + step])
         if kv_dtype == 2:
             out[p0:p0 + step] = oracle.dequantize_rows_int4(*oracle.quantize_rows_int4(x))
+        elif kv_dtype == 3:
+            out[p0:p0 + step] = oracle.dequantize_rows_int8(*oracle.quantize_rows_int8(x))
         else:
             codes, scales = oracle.quantize_rows(x)
             out[p0:p0 + step] = oracle.dequantize_rows(codes, scales)

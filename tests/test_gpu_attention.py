@@ -235,18 +235,20 @@ def test_fp8_cache_decode(hq, hkv, d):
         duo.duo_cache_destroy(handle)
 
 
+@pytest.mark.parametrize("kv_dtype", [2, 3])
 @pytest.mark.parametrize("hq,hkv,d,batch,n_fill", [(8, 2, 128, 2, 700), (32, 8, 128, 1, 4200), (8, 4, 64, 3, 1111)])
-def test_int4_cache_decode(hq, hkv, d, batch, n_fill):
-    # 4-bit cache: fill by append, decode with the fused step (which quantises the new token itself)
-    # and with append-then-attend; the oracle attends over its own codec's round trip of the history
+def test_int4_and_int8_cache_decode(hq, hkv, d, batch, n_fill, kv_dtype):
+    # integer-code caches: fill by append, decode with the fused step (which quantises the new token
+    # itself) and with append-then-attend; the oracle attends over its own codec's round trip
     mask = np.array([(h + 1) % 2 for h in range(hkv)], dtype=np.uint8)
-    _decode_vs_oracle(hq, hkv, d, 8, 40, batch, n_fill, 5, 2, mask)
-    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=8, recent=40, mask=mask, max_seq=n_fill + 3, kv_dtype=2)
+    _decode_vs_oracle(hq, hkv, d, 8, 40, batch, n_fill, 5, kv_dtype, mask)
+    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=8, recent=40, mask=mask, max_seq=n_fill + 3,
+               kv_dtype=kv_dtype)
     q, k, v = make_qkv(77, batch, n_fill + 3, hq, hkv, d)
     out, lse, handle = run_scenario_decode_only(cfg, q, k, v, n_fill, 3)
     for b in range(batch):
         want_o, want_lse = oracle_rows(cfg, q, k, v, np.arange(n_fill, n_fill + 3), b)
-        assert_close(out[b], want_o, "int4 batch %d" % b)
+        assert_close(out[b], want_o, "kv_dtype %d batch %d" % (kv_dtype, b))
         assert np.abs(lse[b] - want_lse).max() <= ATOL_LSE
 
 
@@ -306,7 +308,7 @@ def _decode_vs_oracle(hq, hkv, d, sink, recent, batch, n_fill, n_decode, kv_dtyp
         assert np.abs(got_lse[b] - want_lse).max() <= ATOL_LSE
 
 
-@pytest.mark.parametrize("d,kv_dtype", [(64, 0), (128, 0), (128, 1), (64, 2), (128, 2)])
+@pytest.mark.parametrize("d,kv_dtype", [(64, 0), (128, 0), (128, 1), (64, 2), (128, 2), (64, 3), (128, 3)])
 def test_matrix_core_decode_kernel_with_one_query_head_per_kv_head(d, kv_dtype):
     # the matrix-core kernel forced onto an MHA layer (it pads the single head to 16 columns);
     # the context starts empty-ish, crosses the 32-row unit size and wraps the ring
@@ -316,7 +318,7 @@ def test_matrix_core_decode_kernel_with_one_query_head_per_kv_head(d, kv_dtype):
     _decode_vs_oracle(4, 4, d, 5, 40, 1, 1500, 4, kv_dtype, mask, kernel=1, splits=7)
 
 
-@pytest.mark.parametrize("kv_dtype", [0, 1, 2])
+@pytest.mark.parametrize("kv_dtype", [0, 1, 2, 3])
 def test_query_group_of_eight(kv_dtype):
     mask = np.array([0, 1], dtype=np.uint8)
     _decode_vs_oracle(16, 2, 128, 4, 28, 2, 333, 6, kv_dtype, mask)

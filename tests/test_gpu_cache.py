@@ -11,13 +11,15 @@ pytestmark = pytest.mark.gpu
 
 
 def _export(handle, layer, b, h, d, fp8, capacity):
-    """fp8: the cache's kv_dtype (0 bf16, 1 fp8: d code bytes + a scale, 2 int4: d/2 bytes + (scale, lo))."""
+    """fp8: the cache's kv_dtype (0 bf16, 1 fp8: d code bytes + a scale, 2 int4: d/2 bytes + (scale, lo),
+    3 int8: d bytes + (scale, lo))."""
     import torch
     if fp8:
-        ko = torch.zeros((capacity, d // fp8), dtype=torch.uint8, device="cuda")
-        vo = torch.zeros((capacity, d // fp8), dtype=torch.uint8, device="cuda")
-        ks = torch.zeros((capacity, fp8) if fp8 == 2 else capacity, dtype=torch.float32, device="cuda")
-        vs = torch.zeros((capacity, fp8) if fp8 == 2 else capacity, dtype=torch.float32, device="cuda")
+        width = d // 2 if fp8 == 2 else d
+        ko = torch.zeros((capacity, width), dtype=torch.uint8, device="cuda")
+        vo = torch.zeros((capacity, width), dtype=torch.uint8, device="cuda")
+        ks = torch.zeros((capacity, 2) if fp8 >= 2 else capacity, dtype=torch.float32, device="cuda")
+        vs = torch.zeros((capacity, 2) if fp8 >= 2 else capacity, dtype=torch.float32, device="cuda")
     else:
         ko = torch.zeros((capacity, d), dtype=torch.bfloat16, device="cuda")
         vo = torch.zeros((capacity, d), dtype=torch.bfloat16, device="cuda")
@@ -40,6 +42,8 @@ def _export(handle, layer, b, h, d, fp8, capacity):
     (64, 4, 16, 64, [200, 1, 77], 1),
     (128, 8, 4, 8, [3, 40, 1, 1, 13], 2),
     (64, 4, 16, 64, [200, 1, 77], 2),
+    (128, 8, 4, 8, [3, 40, 1, 1, 13], 3),
+    (64, 4, 16, 64, [200, 1, 77], 3),
 ])
 def test_append_then_export_matches_cache_model(d, hkv, sink, recent, appends, fp8):
     import torch
@@ -74,10 +78,12 @@ def test_append_then_export_matches_cache_model(d, hkv, sink, recent, appends, f
                         assert got_pos.tolist() == want_pos
                         if not fp8:
                             assert np.array_equal(gk, want_k) and np.array_equal(gv, want_v)
-                        elif fp8 == 2:
-                            ck, sk, lk = oracle.quantize_rows_int4(synth.bf16_bits_to_f32(want_k))
-                            cv, sv, lv = oracle.quantize_rows_int4(synth.bf16_bits_to_f32(want_v))
-                            assert np.array_equal(gk, oracle.pack_int4(ck)) and np.array_equal(gv, oracle.pack_int4(cv))
+                        elif fp8 >= 2:
+                            quant = oracle.quantize_rows_int4 if fp8 == 2 else oracle.quantize_rows_int8
+                            pack = oracle.pack_int4 if fp8 == 2 else (lambda c: c)
+                            ck, sk, lk = quant(synth.bf16_bits_to_f32(want_k))
+                            cv, sv, lv = quant(synth.bf16_bits_to_f32(want_v))
+                            assert np.array_equal(gk, pack(ck)) and np.array_equal(gv, pack(cv))
                             for got_par, want_par in ((gks[:, 0], sk), (gks[:, 1], lk), (gvs[:, 0], sv), (gvs[:, 1], lv)):
                                 assert np.array_equal(np.ascontiguousarray(got_par).view(np.uint32),
                                                       np.ascontiguousarray(want_par).view(np.uint32))

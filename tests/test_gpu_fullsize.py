@@ -186,6 +186,10 @@ def test_llama3_8b_shape_decode_at_3300000_context_32_layers_int4():
     _long_context_stack(3300000, duo.DUO_KV_INT4, 32, check_layers=(9,), seed=6)
 
 
+def test_llama3_8b_shape_decode_at_2m_context_32_layers_int8():
+    _long_context_stack(1 << 21, duo.DUO_KV_INT8, 32, check_layers=(23,), seed=7)
+
+
 @pytest.mark.parametrize("hq,hkv,block", [(32, 8, 128), (32, 32, 0)])
 def test_gate_mixed_forward_at_training_length(hq, hkv, block):
     # the identification-phase forward at the longest training length of the appendix (32000 tokens),
