@@ -485,14 +485,17 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         const int sc = sidx < nsplit ? sidx : nsplit - 1;
         mlv[j] = ml[sc];
         x[j] = po[(int64_t)sc * TPR];
-        if (sidx >= nsplit) mlv[j] = make_float2(-INFINITY, 0.f);
       }
 #pragma unroll
       for (int j = 0; j < B4; ++j) {
-        const float mn = fmaxf(mr, mlv[j].x);
+        // rows past the end count as empty; decided here, after every load of the batch has
+        // been issued, so that no load waits for the one before it
+        const bool there = s0 + j * NP < nsplit;
+        const float mj = there ? mlv[j].x : -INFINITY, lj = there ? mlv[j].y : 0.f;
+        const float mn = fmaxf(mr, mj);
         const float mu = mn == -INFINITY ? 0.f : mn;
-        const float a1 = fast_exp2(mr - mu), a2 = fast_exp2(mlv[j].x - mu);
-        lr = lr * a1 + mlv[j].y * a2;
+        const float a1 = fast_exp2(mr - mu), a2 = fast_exp2(mj - mu);
+        lr = lr * a1 + lj * a2;
         acc.x = acc.x * a1 + x[j].x * a2; acc.y = acc.y * a1 + x[j].y * a2;
         acc.z = acc.z * a1 + x[j].z * a2; acc.w = acc.w * a1 + x[j].w * a2;
         mr = mn;

@@ -837,14 +837,17 @@ __global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_
               const int64_t pr = first + (int64_t)sc * G;
               mlv[j] = ml[pr];
               x[j] = po[pr * TPR + dq];
-              if (sidx >= n_parts) mlv[j] = make_float2(-INFINITY, 0.f);
             }
 #pragma unroll
             for (int j = 0; j < B4; ++j) {
-              const float mn = fmaxf(mr, mlv[j].x);
+              // rows past the end count as empty; decided here, after every load of the batch has
+              // been issued, so that no load waits for the one before it
+              const bool there = s0 + j * NP < n_parts;
+              const float mj = there ? mlv[j].x : -INFINITY, lj = there ? mlv[j].y : 0.f;
+              const float mn = fmaxf(mr, mj);
               const float mu = mn == -INFINITY ? 0.f : mn;
-              const float a1 = fast_exp2(mr - mu), a2 = fast_exp2(mlv[j].x - mu);
-              lr = lr * a1 + mlv[j].y * a2;
+              const float a1 = fast_exp2(mr - mu), a2 = fast_exp2(mj - mu);
+              lr = lr * a1 + lj * a2;
               acc.x = acc.x * a1 + x[j].x * a2; acc.y = acc.y * a1 + x[j].y * a2;
               acc.z = acc.z * a1 + x[j].z * a2; acc.w = acc.w * a1 + x[j].w * a2;
               mr = mn;
