@@ -123,12 +123,8 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   constexpr int LPR = D / EPL;         // lanes per row
   constexpr int RPL = 64 / LPR;        // rows per wavefront load
   constexpr int RPB = 4 * RPL;         // rows per block iteration (4 wavefronts)
-#ifdef DUO_EXP_U
-  constexpr int U = DUO_EXP_U;
-#else
   // row iterations per register buffer: as many as fit beside the per-head state
   constexpr int U = (FP8 && G == 2) ? 2 : 4;
-#endif
   constexpr int STEP = RPB * U;        // rows per buffer
   const LayerView& lv = a.lv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

@@ -169,11 +169,8 @@ struct KeyParams {
   float ks[8], klo[8], vs[8], vlo[8];
 };
 
-#ifndef DUO_EXP_INT4_OCC
-#define DUO_EXP_INT4_OCC 1
-#endif
 template <int D, int MODE>
-__global__ __launch_bounds__(256, MODE == 2 ? DUO_EXP_INT4_OCC : 1) void decode_sk_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
   using S = Shape<D, MODE>;
   constexpr bool FP8 = MODE == 1, INT4 = MODE == 2, INT8 = MODE == 3, QUANT = MODE != 0;
   constexpr bool ASYM = INT4 || INT8;    // integer codes with (scale, lo) per row

@@ -63,9 +63,10 @@ __device__ inline HalfPair both_halves(float x) {
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
   return HalfPair{a, b};
 }
-#ifndef DUO_EXP_NW
-#define DUO_EXP_NW 8
-#endif
+// Wavefronts per workgroup with 32 query rows each (two per SIMD), and 32-row sub-blocks per
+// wavefront in the instantiations that are launched.
+constexpr int kWaves = 8;
+constexpr int kSubBlocks = 1;
 // LDS reads of the matrix-core phase are written as inline assembly with hand-placed waits:
 // the compiler would tie them to the outstanding LDS-direct loads of later tiles (draining the
 // prefetch) and would not keep reads several products ahead of their use.  The wait helpers
@@ -147,13 +148,13 @@ struct Geometry {
 };
 
 template <int D, int NG, int NSB>
-__global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_EXP_NW == 4) ? 2 : 1) void prefill_kernel(PrefillArgs a) {
+__global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kernel(PrefillArgs a) {
   using Geo = Geometry<D>;
   constexpr int ROW = Geo::ROW, TILE = Geo::TILE, BUF_BYTES = Geo::BUF_BYTES;
   constexpr int NKK = D / 16;          // MFMA k-steps of the QK^T contraction
   constexpr int NMB = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;           // 16-byte pieces per row
-  constexpr int NW = NSB == 2 ? 4 : DUO_EXP_NW; // wavefronts per workgroup: 64 rows each, or 32 rows each at two per SIMD
+  constexpr int NW = NSB == 2 ? 4 : kWaves; // wavefronts per workgroup: 64 rows each, or 32 rows each at two per SIMD
   constexpr int WPG = NW / NG;         // wavefronts per key group
   constexpr int RW = 32 * NSB;         // query rows per wavefront
   constexpr int BM = RW * WPG;         // query rows per workgroup
@@ -659,7 +660,7 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : DUO_EXP_NW * 64, (NSB == 1 && DUO_
 
 template <int D, int NG, int NSB>
 hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
-  constexpr int NW = NSB == 2 ? 4 : DUO_EXP_NW;
+  constexpr int NW = NSB == 2 ? 4 : kWaves;
   constexpr int BM = 32 * NSB * (NW / NG);
   constexpr int lds = NG * 2 * Geometry<D>::BUF_BYTES;
   static bool configured = false;   // one attribute call per kernel instantiation and process
@@ -675,10 +676,6 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
   prefill_kernel<D, NG, NSB><<<grid, NW * 64, lds, stream>>>(a);
   return hipGetLastError();
 }
-
-#ifndef DUO_EXP_NSB
-#define DUO_EXP_NSB 1
-#endif
 
 // out = alpha * out + (1 - alpha) * other, eight bf16 values per thread
 __global__ __launch_bounds__(256) void gate_mix_kernel(GateMixArgs a) {
@@ -711,18 +708,13 @@ hipError_t launch_gate_mix(const GateMixArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
-  constexpr int NSB = DUO_EXP_NSB;
-#ifdef DUO_EXP_NG1
-  if (a.lv.head_dim == 128) return launch_one<128, 1, NSB>(a, stream);
-  return launch_one<64, 1, NSB>(a, stream);
-#else
+  constexpr int NSB = kSubBlocks;
   // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
   const int n_heavy_heads = a.force_class == 1 ? a.lv.n_kv_heads : (a.force_class == 2 ? 0 : a.lv.n_ret);
   const int64_t heavy_blocks = (int64_t)a.lv.batch * n_heavy_heads * a.lv.group * ((a.n + 255) / 256);
   const bool split_keys = heavy_blocks < 384;
   if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB>(a, stream) : launch_one<128, 1, NSB>(a, stream);
   return split_keys ? launch_one<64, 2, NSB>(a, stream) : launch_one<64, 1, NSB>(a, stream);
-#endif
 }
 
 }  // namespace duo
