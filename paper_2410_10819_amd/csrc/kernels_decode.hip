@@ -50,6 +50,16 @@ __device__ inline int uniform_load(const int32_t* p) {
 __device__ inline void coherent_store(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Their counterpart: device-scope loads are served from the memory side of the per-die L2
+// caches, so what another die stored this way is seen without invalidating a cache first.
+__device__ inline float2 coherent_load2(const float2* p) {
+  const uint64_t v = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+}
+__device__ inline float4 coherent_load4(const float4* p) {
+  const float2 lo = coherent_load2((const float2*)p), hi = coherent_load2((const float2*)p + 1);
+  return make_float4(lo.x, lo.y, hi.x, hi.y);
+}
 
 
 // fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448.
@@ -451,8 +461,8 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   }
   __syncthreads();
   if (!sm_last) return;
-  // Acquire: drop any stale cached copies of the partials before reading them.
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  // The partials are read with device-scope loads (after the ticket, on which this branch
+  // depends), so no cached copy of an earlier launch's partials can be hit.
   // All heads of the group at once, one memory round trip: the 256 threads form
   // SLOTS rows of TPR threads (one float4 of a partial row each); head g owns NP
   // consecutive slots, slot `part` of a head sums the partials part, part + NP, ...
@@ -479,8 +489,8 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
       for (int j = 0; j < B4; ++j) {
         const int sidx = s0 + j * NP;
         const int sc = sidx < nsplit ? sidx : nsplit - 1;
-        mlv[j] = ml[sc];
-        x[j] = po[(int64_t)sc * TPR];
+        mlv[j] = coherent_load2(ml + sc);
+        x[j] = coherent_load4(po + (int64_t)sc * TPR);
       }
 #pragma unroll
       for (int j = 0; j < B4; ++j) {

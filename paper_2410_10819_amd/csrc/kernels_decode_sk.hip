@@ -808,6 +808,8 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
       }
       __syncthreads();
       if (sm_last) {
+        // Acquire, then plain 16-byte loads: with dozens of partial rows per head the merge is bound
+        // by what one compute unit can fetch, and device-scope loads (8 bytes at most) were slower.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         // All heads of the group at once: 256 threads = SLOTS rows of TPR threads (one float4 of a
         // partial row each); head g owns NP consecutive slots; slot `part` of a head folds the
