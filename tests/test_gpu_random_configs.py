@@ -83,3 +83,43 @@ def test_random_prefill_configurations(hq, hkv, d, sink, recent, batch, chunks, 
         assert np.abs(lse[b][:, :total] - want_lse).max() <= ATOL_LSE
         want_d, _ = oracle_rows(cfg, q, k, v, np.arange(total, total + n_decode), b)
         assert_close(synth.bf16_bits_to_f64(out[b][total:]), want_d, "decode after deployed prefill")
+
+
+def _gate_cases():
+    rng = np.random.default_rng(20241012)
+    cases = []
+    for i in range(8):
+        hkv, group, d, sink, recent, _ = _draw_shape(rng)
+        t = int(rng.integers(20, 900))
+        block = int(rng.choice([0, 0, 1, 5, 16, 64, 128]))
+        batch = int(rng.integers(1, 3))
+        alpha = rng.uniform(0, 1, hkv).astype(np.float32)
+        alpha[int(rng.integers(0, hkv))] = float(rng.integers(0, 2))    # one gate at an end of the range
+        cases.append(pytest.param(hkv * group, hkv, d, sink, recent, batch, t, alpha, block, i,
+                                  id="%d-h%dx%d-d%d-s%d-r%d-b%d-t%d-blk%d" % (i, hkv, group, d, sink, recent, batch, t, block)))
+    return cases
+
+
+@pytest.mark.parametrize("hq,hkv,d,sink,recent,batch,t,alpha,block,seed", _gate_cases())
+def test_random_gate_mixed_configurations(hq, hkv, d, sink, recent, batch, t, alpha, block, seed):
+    from test_gpu_gate_mixed import _run
+    _run(hq, hkv, d, sink, recent, batch, t, alpha, block, seed=3000 + seed)
+
+
+def _cache_cases():
+    rng = np.random.default_rng(20241013)
+    cases = []
+    for i in range(8):
+        hkv, _, d, sink, recent, _ = _draw_shape(rng)
+        kv_dtype = int(rng.integers(0, 4))
+        appends = [int(x) for x in rng.choice([1, 1, 2, 5, 33, 64, 150, 400], size=int(rng.integers(2, 6)))]
+        cases.append(pytest.param(d, hkv, sink, recent, appends, kv_dtype,
+                                  id="%d-h%d-d%d-s%d-r%d-kv%d-%s" % (i, hkv, d, sink, recent, kv_dtype,
+                                                                     "+".join(map(str, appends)))))
+    return cases
+
+
+@pytest.mark.parametrize("d,hkv,sink,recent,appends,kv_dtype", _cache_cases())
+def test_random_append_sequences_leave_the_model_contents(d, hkv, sink, recent, appends, kv_dtype):
+    from test_gpu_cache import test_append_then_export_matches_cache_model as check
+    check(d, hkv, sink, recent, appends, kv_dtype)
