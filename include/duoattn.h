@@ -117,7 +117,11 @@ int duo_kv_append(duo_cache_t* cache, int layer, const void* k, const void* v,
  * up to their own position; streaming heads see the Lambda mask exactly,
  * whatever the chunk size.  The cache is NOT modified: call duo_kv_append with
  * the same k, v afterwards.  out: bf16, shape of q.  lse: fp32
- * [batch, n_q_heads, n_new] natural-log-sum-exp of the scaled scores, or NULL. */
+ * [batch, n_q_heads, n_new] natural-log-sum-exp of the scaled scores, or NULL.
+ * On a quantised cache the cached positions are attended to as the cache holds them
+ * (code * scale [+ minimum], rounded to bf16) and the chunk's own positions as given; the
+ * first such call allocates a bf16 image of one layer's caches (DUO_ENOMEM if that fails),
+ * which the handle keeps, and every call refreshes it from the codes on `stream`. */
 int duo_attn_prefill(duo_cache_t* cache, int layer, const void* q, const void* k,
                      const void* v, int n_new, const duo_call_params_t* params,
                      void* out, float* lse, void* stream);

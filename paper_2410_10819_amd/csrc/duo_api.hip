@@ -45,6 +45,8 @@ struct duo_cache {
   int user_splits = 0;
   bool force_matrix_decode = false;
   int64_t cache_bytes = 0;
+  // bf16 image of one quantised layer's rows for pre-filling (allocated at the first such call)
+  void* deq[4] = {nullptr, nullptr, nullptr, nullptr};   // K retrieval, V retrieval, K streaming, V streaming
 };
 
 namespace {
@@ -354,10 +356,40 @@ static int prefill_common(duo_cache_t* c, int layer, const void* q, const void* 
   if (L.len + n_new > c->cfg.max_seq)
     return fail(DUO_ERANGE, "chunk of %d tokens at length %lld exceeds max_seq %lld", n_new,
                 (long long)L.len, (long long)c->cfg.max_seq);
-  if (c->cfg.kv_dtype != DUO_KV_BF16)
-    return fail(DUO_EINVAL, "duo_attn_prefill supports bf16 caches only");
+  duo::LayerView view = L.view;
+  if (c->cfg.kv_dtype != DUO_KV_BF16) {
+    // The pre-filling kernel reads bf16 rows: the rows the layer holds are widened into a scratch
+    // image first (a few bytes of traffic per cached row against the chunk's attention over it),
+    // and the kernel runs on that image; the chunk's own rows are attended to as given.
+    if (!c->deq[0]) {
+      int max_ret = 0, max_str = 0;
+      for (const Layer& x : c->layers) { max_ret = std::max(max_ret, x.view.n_ret); max_str = std::max(max_str, x.view.n_str); }
+      const size_t row = (size_t)c->cfg.head_dim * 2;
+      const size_t ret_bytes = (size_t)c->cfg.batch * max_ret * (size_t)c->cfg.max_seq * row;
+      const size_t str_bytes = (size_t)c->cfg.batch * max_str * ((size_t)c->cfg.sink + c->cfg.recent) * row;
+      const size_t want[4] = {ret_bytes, ret_bytes, str_bytes, str_bytes};
+      for (int i = 0; i < 4; ++i) {
+        hipError_t e = dev_alloc(c, &c->deq[i], want[i]);
+        if (e != hipSuccess) {
+          // what was allocated stays owned by the handle; the next call tries again from the start
+          for (int j = 0; j < 4; ++j) c->deq[j] = nullptr;
+          return fail(e == hipErrorOutOfMemory ? DUO_ENOMEM : DUO_EHIP,
+                      "hipMalloc of %zu bytes for the bf16 image of a quantised layer failed: %s", want[i],
+                      hipGetErrorString(e));
+        }
+      }
+    }
+    if (L.len > 0) {
+      hipError_t e = duo::launch_dequant(L.view, L.len, c->deq[0], c->deq[1], c->deq[2], c->deq[3], (hipStream_t)stream);
+      if (e != hipSuccess) return fail_hip(e, "dequantisation launch");
+    }
+    view.k_ret = (uint8_t*)c->deq[0]; view.v_ret = (uint8_t*)c->deq[1];
+    view.k_str = (uint8_t*)c->deq[2]; view.v_str = (uint8_t*)c->deq[3];
+    view.ks_ret = view.vs_ret = view.ks_str = view.vs_str = nullptr;
+    view.row_bytes = c->cfg.head_dim * 2; view.kv_mode = DUO_KV_BF16; view.sc_per_row = 0;
+  }
   duo::PrefillArgs a;
-  a.lv = L.view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
+  a.lv = view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
   a.chunk_causal = chunk_causal ? 1 : 0;
   a.force_class = 0; a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
   hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);

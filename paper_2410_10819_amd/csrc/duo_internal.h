@@ -104,6 +104,11 @@ hipError_t launch_export(const LayerView& lv, int batch_idx, int kv_head, int64_
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_sk(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
+// Widen the rows a quantised layer holds (cache length len) to bf16 rows in the same layouts:
+// k_ret_out / v_ret_out [batch][n_ret][max_seq][head_dim] and k_str_out / v_str_out
+// [batch][n_str][sink + recent][head_dim], bf16.  Rows beyond the ones held are not written.
+hipError_t launch_dequant(const LayerView& lv, int64_t len, void* k_ret_out, void* v_ret_out, void* k_str_out,
+                          void* v_str_out, hipStream_t stream);
 
 // Number of rows a streaming cache holds after `len` appends.
 __host__ __device__ inline int64_t streaming_rows(int64_t len, int sink, int recent) {

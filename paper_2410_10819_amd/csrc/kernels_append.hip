@@ -215,7 +215,78 @@ __global__ __launch_bounds__(256) void export_kernel(LayerView lv, int batch_idx
   }
 }
 
+// bf16 image of quantised rows: value = code * scale (fp8) or code * scale + minimum (int4, int8),
+// in fp32, rounded to nearest even.  One 16-byte piece of output (8 values) per thread; a segment
+// is one (sequence, head) run of `seg_stride` rows of which the first `rows` are widened.
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes, const float* __restrict__ params,
+                                                      uint4* __restrict__ out, int head_dim, int64_t n_seg,
+                                                      int64_t seg_stride, int64_t rows) {
+  const int ppr = head_dim / 8;   // pieces per row
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n_seg * rows * ppr) return;
+  const int piece = (int)(idx % ppr);
+  const int64_t r = idx / ppr;
+  const int64_t row = (r / rows) * seg_stride + r % rows;
+  float f[8];
+  if constexpr (MODE == 2) {
+    const uint32_t w = *(const uint32_t*)(codes + row * (head_dim / 2) + piece * 4);
+    const float2 sl = *(const float2*)(params + row * 2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) f[j] = fmaf((float)((w >> (4 * j)) & 0xFu), sl.x, sl.y);
+  } else {
+    const uint2 w = *(const uint2*)(codes + row * head_dim + piece * 8);
+    const uint32_t ww[2] = {w.x, w.y};
+    if constexpr (MODE == 3) {
+      const float2 sl = *(const float2*)(params + row * 2);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) f[j] = fmaf((float)((ww[j / 4] >> (8 * (j % 4))) & 0xFFu), sl.x, sl.y);
+    } else {
+      const float sc = params[row];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const auto a = __builtin_amdgcn_cvt_pk_f32_fp8((int)ww[i], false);
+        const auto b = __builtin_amdgcn_cvt_pk_f32_fp8((int)ww[i], true);
+        f[4 * i] = a[0] * sc; f[4 * i + 1] = a[1] * sc; f[4 * i + 2] = b[0] * sc; f[4 * i + 3] = b[1] * sc;
+      }
+    }
+  }
+  out[row * ppr + piece] = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                                      pack_bf16x2(f[6], f[7]));
+}
+
 }  // namespace
+
+hipError_t launch_dequant(const LayerView& lv, int64_t len, void* k_ret_out, void* v_ret_out, void* k_str_out,
+                          void* v_str_out, hipStream_t stream) {
+  if (lv.kv_mode < 1 || lv.kv_mode > 3) return hipErrorInvalidValue;
+  const int64_t cap = (int64_t)lv.sink + lv.recent;
+  struct { const uint8_t* codes; const float* params; void* out; int64_t n_seg, stride, rows; } parts[] = {
+      {lv.k_ret, lv.ks_ret, k_ret_out, (int64_t)lv.batch * lv.n_ret, lv.max_seq, len},
+      {lv.v_ret, lv.vs_ret, v_ret_out, (int64_t)lv.batch * lv.n_ret, lv.max_seq, len},
+      {lv.k_str, lv.ks_str, k_str_out, (int64_t)lv.batch * lv.n_str, cap, streaming_rows(len, lv.sink, lv.recent)},
+      {lv.v_str, lv.vs_str, v_str_out, (int64_t)lv.batch * lv.n_str, cap, streaming_rows(len, lv.sink, lv.recent)}};
+  for (auto& p : parts) {
+    const int64_t pieces = p.n_seg * p.rows * (lv.head_dim / 8);
+    if (pieces <= 0) continue;
+    if (!p.out) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((pieces + 255) / 256)), block(256);
+    uint4* out = (uint4*)p.out;
+    if (lv.kv_mode == 1) dequant_kernel<1><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.rows);
+    else if (lv.kv_mode == 2) dequant_kernel<2><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.rows);
+    else dequant_kernel<3><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.rows);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
 
 hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int64_t pos0, int n_new,
                          hipStream_t stream) {

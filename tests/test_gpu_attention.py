@@ -361,3 +361,40 @@ def test_deployed_chunk_causal_prefill(hq, hkv, d, sink, recent, chunks, batch):
         # the decode steps after it see the ordinary cache contents
         want_d, _ = oracle_rows(cfg, q, k, v, np.arange(total, total + 4), b)
         assert_close(synth.bf16_bits_to_f64(out[b][total:]), want_d, "decode after deployed prefill")
+
+
+@pytest.mark.parametrize("kv_dtype", [1, 2, 3])
+@pytest.mark.parametrize("hq,hkv,d,sink,recent,chunks,batch,deployed", [
+    (8, 2, 128, 4, 32, [300, 1, 77, 130], 2, False),     # GQA 4, ragged chunks
+    (4, 4, 64, 16, 64, [129, 513, 64], 1, False),        # head_dim 64, tile tails
+    (8, 8, 128, 64, 256, [700, 300], 1, True),           # deployment constants, chunk-causal streaming heads
+])
+def test_prefill_over_a_quantised_cache(hq, hkv, d, sink, recent, chunks, batch, deployed, kv_dtype):
+    # cached positions are seen through the codec (as the cache holds them), the chunk's own positions
+    # as given; the decode steps afterwards see every position through the codec
+    total, n_decode = sum(chunks), 3
+    mask = np.array([(h + 1) % 2 for h in range(hkv)], dtype=np.uint8)
+    cfg = dict(batch=batch, hq=hq, hkv=hkv, d=d, sink=sink, recent=recent, mask=mask, max_seq=total + n_decode,
+               kv_dtype=kv_dtype)
+    q, k, v = make_qkv(77 + kv_dtype, batch, total + n_decode, hq, hkv, d)
+    out, lse, handle = run_scenario(duo, cfg, q, k, v, chunks, n_decode, deployed=deployed, fused_decode="step")
+    duo.duo_cache_destroy(handle)
+    from helpers import oracle_kv
+    for b in range(batch):
+        kq, vq = oracle_kv(k[b], v[b], kv_dtype)          # every position through the codec
+        # pre-filling reads the cached rows from a bf16 image of code * scale (+ minimum)
+        kq, vq = (synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(x.astype(np.float32))) for x in (kq, vq))
+        kf, vf = synth.bf16_bits_to_f64(k[b]), synth.bf16_bits_to_f64(v[b])
+        p0 = 0
+        for n in chunks:
+            k_hist = np.concatenate([kq[:p0], kf[p0:p0 + n]])
+            v_hist = np.concatenate([vq[:p0], vf[p0:p0 + n]])
+            pos = np.arange(p0, p0 + n)
+            want_o, want_lse = oracle.attention_rows(synth.bf16_bits_to_f64(q[b][pos]), k_hist, v_hist, pos, mask, sink,
+                                                     recent, None,
+                                                     chunk_starts=np.full(n, p0) if deployed else None)
+            assert_close(synth.bf16_bits_to_f64(out[b][pos]), want_o, "chunk at %d, batch %d" % (p0, b))
+            assert np.abs(lse[b][:, pos] - want_lse).max() <= ATOL_LSE
+            p0 += n
+        want_d, _ = oracle_rows(cfg, q, k, v, np.arange(total, total + n_decode), b)
+        assert_close(synth.bf16_bits_to_f64(out[b][total:]), want_d, "decode after the quantised prefill")

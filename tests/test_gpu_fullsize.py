@@ -91,6 +91,41 @@ def test_llama3_8b_shape_128k_prefill_32k_chunks():
     _prefill_and_decode(32, 8, 128, 0.5, 131072, 32768, 0, n_rand=1, seed=0)
 
 
+def test_llama3_8b_shape_128k_prefill_32k_chunks_over_an_int4_cache():
+    # the same pre-filling with the cache in 4-bit codes: cached positions are seen as the cache holds them
+    # (bf16 image of code * scale + minimum), the chunk's own positions as given; sampled rows per chunk
+    import torch
+    hq, hkv, d, n_ctx, chunk, seed = 32, 8, 128, 131072, 32768, 9
+    mask = synth.retrieval_mask(seed, 1, hkv, 0.5)[0]
+    table = device_table()
+    q = device_fill(table, seed, 0, synth.TENSOR_Q, 1, 0, n_ctx, hq, d)
+    k = device_fill(table, seed, 0, synth.TENSOR_K, 1, 0, n_ctx, hkv, d)
+    v = device_fill(table, seed, 0, synth.TENSOR_V, 1, 0, n_ctx, hkv, d)
+    out = torch.empty_like(q)
+    handle = duo.duo_cache_create(1, 1, hq, hkv, d, SINK, RECENT, n_ctx, mask[None], duo.DUO_KV_INT4)
+    try:
+        for p in range(0, n_ctx, chunk):
+            duo.duo_attn_prefill(handle, 0, q[:, p:p + chunk], k[:, p:p + chunk], v[:, p:p + chunk], chunk,
+                                 out[:, p:p + chunk])
+            duo.duo_kv_append(handle, 0, k[:, p:p + chunk], v[:, p:p + chunk], chunk)
+        torch.cuda.synchronize()
+    finally:
+        duo.duo_cache_destroy(handle)
+    rng = np.random.default_rng(seed)
+    kb = cpu_history_bits(seed, 0, synth.TENSOR_K, 0, n_ctx, hkv, d)
+    vb = cpu_history_bits(seed, 0, synth.TENSOR_V, 0, n_ctx, hkv, d)
+    image = lambda bits: synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(oracle_history_f64(bits, 2).astype(np.float32)))
+    kq, vq = image(kb), image(vb)
+    for p in range(0, n_ctx, chunk):
+        positions = np.array(_sample_positions(rng, p, chunk, 2))
+        k_hist = np.concatenate([kq[:p], synth.bf16_bits_to_f64(kb[p:p + chunk])])
+        v_hist = np.concatenate([vq[:p], synth.bf16_bits_to_f64(vb[p:p + chunk])])
+        idx = torch.from_numpy(positions).cuda()
+        _oracle_check(from_dev_bits(q[0, idx]), k_hist, v_hist, positions, mask, from_dev_bits(out[0, idx]), None,
+                      "chunk at %d" % p)
+        del k_hist, v_hist
+
+
 @pytest.mark.parametrize("batch", [1, 4, 16])
 def test_llama3_8b_shape_decode_at_128k_context(batch):
     import torch
