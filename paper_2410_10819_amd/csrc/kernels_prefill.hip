@@ -535,13 +535,25 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
           // up to the start of the first local block for the block-aligned one
           const int win = a.win_block ? (int)(qpos[sb] % a.win_block) + (a.n_local_blocks - 1) * a.win_block + 1
                                       : lv.recent;
+          // An entry at or after n_head holds position entry + gap32, an earlier one its own index.
+          // So the visible entries of the tile are two runs: sink entries [0, s_hi] (not beyond
+          // the list or the query) and window entries [w_lo, w_hi] (the `win` positions ending at
+          // the query; behind a gap only entries from n_head on).  A lane's entries are a
+          // compile-time constant plus 4 * half, which goes into the bounds once: three
+          // compares per score.
+          const int qb = qa - gap32;                           // the query's own entry (from n_head on)
+          int s_hi = sink_rel - 1 < lim - 1 ? sink_rel - 1 : lim - 1;
+          s_hi = s_hi < qa ? s_hi : qa;
+          int w_hi = lim - 1 < qb ? lim - 1 : qb;
+          int w_lo = qb - win + 1;
+          if (gap32 > 0 && w_lo < nh_rel) w_lo = nh_rel;
+          s_hi -= 4 * half; w_hi -= 4 * half; w_lo -= 4 * half;
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const int u_rel = 32 * kb + 8 * (r / 4) + 4 * half + (r % 4);
-              const int diff = qa - u_rel - (u_rel >= nh_rel ? gap32 : 0);   // query pos - key pos
-              const bool vis = u_rel < lim && diff >= 0 && (u_rel < sink_rel || diff < win);
+              const int c = 32 * kb + 8 * (r / 4) + (r % 4);
+              const bool vis = (c <= s_hi) | ((c >= w_lo) & (c <= w_hi));
               if (!vis) sv[kb][r] = -INFINITY;
             }
         }
