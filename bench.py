@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, scaled by a 1 GiB
 # device copy (summaries under profiles/); known for these workloads only.
-MEASURED_TRAFFIC = {"c2": {"decode": 139.14e6 + 0.17e6, "prefill": 172.2e6 + 40.8e6},
+MEASURED_TRAFFIC = {"c2": {"decode": 139.15e6 + 0.17e6, "prefill": 170.2e6 + 33.6e6},
                     "c4": {"decode": 2149.2e6 + 0.6e6},
                     "c6": {"decode": 1902.8e6 + 0.6e6}}
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
