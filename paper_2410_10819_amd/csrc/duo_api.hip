@@ -140,9 +140,12 @@ int choose_ret_workers(const duo_cache* c, const Layer& L, int64_t units_ret) {
   } else {
     // bf16 rows: memory-bound, so the compute units that take the short streaming segments are
     // left out of the count; quantised rows: instruction-bound, every compute unit gets a worker
-    // and the streaming workgroups run as units free up
+    // and the streaming workgroups run as units free up - unless they are so few that leaving
+    // them their units costs less than making them wait for one (measured: 4 of them at batch 1
+    // add 2-3 us behind 256 workers, 64 of them at batch 16 would idle a quarter of the part)
+    const int64_t str_wgs = (int64_t)L.view.n_str * c->cfg.batch;
     int64_t budget = 256;
-    if (c->cfg.kv_dtype == DUO_KV_BF16) budget -= (int64_t)L.view.n_str * c->cfg.batch;
+    if (c->cfg.kv_dtype == DUO_KV_BF16 || str_wgs <= 8) budget -= str_wgs;
     if (budget < 128) budget = 128;
     w = segs <= budget ? segs * (budget / segs) : budget;
     const int64_t by_len = total / kMinUnits;

@@ -92,15 +92,16 @@ __device__ inline uint32_t e4m3_encode(float x) {
   return code | sign;
 }
 
-// Four E4M3 codes (one dword) -> four bf16 values (two dwords); exact.
+// Four E4M3 codes (one dword) -> four bf16 values (two dwords); exact (every E4M3 value has at
+// most 4 significant bits).  The scaled conversion of this architecture turns two codes into a
+// bf16 pair in one instruction; with a scale of one it gives, for every code, the bits of the
+// conversion through fp32 (checked over all code pairs).
 __device__ inline uint2 e4m3x4_to_bf16x4(uint32_t w) {
-  const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-  const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
-  // every E4M3 value has at most 4 significant bits, so the upper halves of the floats are the
-  // bf16 values: one byte permute packs two of them
+  const bf16x2 lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+  const bf16x2 hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
   uint2 r;
-  r.x = __builtin_amdgcn_perm(__float_as_uint(lo[1]), __float_as_uint(lo[0]), 0x07060302u);
-  r.y = __builtin_amdgcn_perm(__float_as_uint(hi[1]), __float_as_uint(hi[0]), 0x07060302u);
+  r.x = __builtin_bit_cast(uint32_t, lo);
+  r.y = __builtin_bit_cast(uint32_t, hi);
   return r;
 }
 
