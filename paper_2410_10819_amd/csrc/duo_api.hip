@@ -111,20 +111,26 @@ int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
 // Rate (bytes per second) at which W workgroups of the even-split decode kernel, one per compute
 // unit, stream bf16 cache rows together: measured on the part at 128K context - about 52 GB/s per
 // workgroup while they are few, 7 TB/s from about 220 workgroups on.
-double decode_stream_rate(int64_t W) {
+// Quantised rows are bound by a workgroup's instructions before the memory system saturates:
+// about 30 GB/s per workgroup with one code byte per value, 20 GB/s with two codes per byte.
+double decode_stream_rate(int64_t W, int kv_dtype) {
   static const double w_pts[] = {0, 64, 96, 128, 160, 192, 224, 256};
   static const double r_pts[] = {0, 3.57e12, 5.06e12, 6.2e12, 6.6e12, 6.9e12, 7.0e12, 7.0e12};
-  if (W >= 256) return r_pts[7];
-  int i = 0;
-  while (w_pts[i + 1] < (double)W) ++i;
-  const double f = ((double)W - w_pts[i]) / (w_pts[i + 1] - w_pts[i]);
-  return r_pts[i] + f * (r_pts[i + 1] - r_pts[i]);
+  double r = r_pts[7];
+  if (W < 256) {
+    int i = 0;
+    while (w_pts[i + 1] < (double)W) ++i;
+    const double f = ((double)W - w_pts[i]) / (w_pts[i + 1] - w_pts[i]);
+    r = r_pts[i] + f * (r_pts[i + 1] - r_pts[i]);
+  }
+  if (kv_dtype != DUO_KV_BF16) r = std::min(r, (double)W * (kv_dtype == DUO_KV_INT4 ? 20e9 : 30e9));
+  return r;
 }
 
 // Workgroups that share the retrieval rows in the even-split decode kernel: one resident
 // workgroup per compute unit together with the streaming workgroups, a whole number per
 // segment while segments are few (no workgroup then crosses a segment border), and at least
-// kMinUnits units of 32 rows each.  On bf16 rows with few segments the count per segment is the
+// kMinUnits units of 32 rows each.  With few segments the count per segment is the
 // one that minimises streaming time plus merge time: the last workgroup of a segment fetches one
 // partial row per workgroup and query head, at the 45 GB/s a single compute unit gets for such
 // data, so at 128K context 56 workgroups per segment beat 63 and one segment is best served by
@@ -150,14 +156,14 @@ int choose_ret_workers(const duo_cache* c, const Layer& L, int64_t units_ret) {
     w = segs <= budget ? segs * (budget / segs) : budget;
     const int64_t by_len = total / kMinUnits;
     if (w > by_len) w = segs <= by_len ? segs * (by_len / segs) : by_len;
-    if (c->cfg.kv_dtype == DUO_KV_BF16 && segs <= 8 && w >= 2 * segs) {
-      const double bytes = (double)total * duo::kDecodeUnitRows * L.view.row_bytes * 2.0;
+    if (segs <= 8 && w >= 2 * segs) {
+      const double bytes = (double)total * duo::kDecodeUnitRows * (L.view.row_bytes + 4.0 * L.view.sc_per_row) * 2.0;
       const double merge_per_part = (double)L.view.group * (L.view.head_dim + 2) * sizeof(float) / 45e9;
       const int64_t per_max = w / segs;
       int64_t best = per_max;
-      double best_t = bytes / decode_stream_rate(w) + (double)per_max * merge_per_part;
+      double best_t = bytes / decode_stream_rate(w, c->cfg.kv_dtype) + (double)per_max * merge_per_part;
       for (int64_t per = per_max - 1; per >= 1; --per) {
-        const double t = bytes / decode_stream_rate(segs * per) + (double)per * merge_per_part;
+        const double t = bytes / decode_stream_rate(segs * per, c->cfg.kv_dtype) + (double)per * merge_per_part;
         if (t < best_t) { best_t = t; best = per; }
       }
       w = segs * best;
