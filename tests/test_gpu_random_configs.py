@@ -23,11 +23,19 @@ def _draw_shape(rng):
     return hkv, group, d, sink, recent, mask
 
 
+def _draw_wide_shape(rng):
+    """Like _draw_shape with sink counts and windows of several tiles (and windows longer than the fill)."""
+    hkv, group, d, _, _, mask = _draw_shape(rng)
+    sink = int(rng.choice([0, 63, 64, 65, 128, 200, 300]))
+    recent = int(rng.choice([127, 128, 129, 256, 300, 511, 600]))
+    return hkv, group, d, sink, recent, mask
+
+
 def _decode_cases():
     rng = np.random.default_rng(20241010)
     cases = []
-    for i in range(24):
-        hkv, group, d, sink, recent, mask = _draw_shape(rng)
+    for i in range(34):
+        hkv, group, d, sink, recent, mask = _draw_shape(rng) if i < 24 else _draw_wide_shape(rng)
         kv_dtype = int(rng.choice([0, 0, 0, 1, 2, 3]))
         batch = int(rng.integers(1, 4))
         n_fill = int(rng.choice([0, 1, 31, 32, 33, 200, 777, 1500, 2600]))
@@ -50,8 +58,8 @@ def test_random_decode_configurations(hq, hkv, d, sink, recent, batch, n_fill, k
 def _prefill_cases():
     rng = np.random.default_rng(20241011)
     cases = []
-    for i in range(14):
-        hkv, group, d, sink, recent, mask = _draw_shape(rng)
+    for i in range(22):
+        hkv, group, d, sink, recent, mask = _draw_shape(rng) if i < 14 else _draw_wide_shape(rng)
         batch = int(rng.integers(1, 3))
         total = int(rng.integers(40, 1300))
         n_chunks = int(rng.integers(1, 6))
