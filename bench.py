@@ -27,7 +27,11 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, scaled by a 1 GiB
 # device copy (summaries under profiles/); known for these workloads only.
 MEASURED_TRAFFIC = {"c2": {"decode": 139.15e6 + 0.17e6, "prefill": 170.2e6 + 33.6e6},
+                    "c3_prefill": {"prefill": 2527.9e6 + 268.7e6},
+                    "c3_decode_b1": {"decode": 270.26e6 + 0.54e6},
+                    "c3_decode_b16": {"decode": 4308.0e6 + 0.65e6},
                     "c4": {"decode": 2149.2e6 + 0.6e6},
+                    "c5": {"decode": 3500.7e6 + 0.56e6},
                     "c6": {"decode": 1902.8e6 + 0.6e6}}
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
