@@ -126,10 +126,11 @@ def test_llama3_8b_shape_128k_prefill_32k_chunks_over_an_int4_cache():
         del k_hist, v_hist
 
 
-@pytest.mark.parametrize("batch", [1, 4, 16])
-def test_llama3_8b_shape_decode_at_128k_context(batch):
+@pytest.mark.parametrize("batch,n_ctx", [(1, 131072), (4, 131072), (16, 131072), (16, 524288)])
+def test_llama3_8b_shape_decode_at_128k_context(batch, n_ctx):
+    # the last case makes each of the layer's K and V arrays 8.6 GB: byte offsets beyond 32 bits
     import torch
-    hq, hkv, d, n_ctx, seed = 32, 8, 128, 131072, 3
+    hq, hkv, d, seed = 32, 8, 128, 3
     mask = synth.retrieval_mask(seed, 1, hkv, 0.5)[0]
     table = device_table()
     handle = duo.duo_cache_create(1, batch, hq, hkv, d, SINK, RECENT, n_ctx + 2, mask[None])
