@@ -157,6 +157,48 @@ def test_llama3_8b_shape_decode_at_128k_context(batch, n_ctx):
                           "batch %d of %d, token %d" % (b, batch, t))
 
 
+def test_prefill_chunk_over_caches_beyond_4_gib():
+    # batch 8 at 1M context: each of the layer's K and V retrieval arrays is 8.6 GB, and the checked sequence
+    # (the last one) lies wholly beyond 32-bit byte offsets; one 2048-token chunk, sampled rows, one
+    # retrieval and one streaming KV group
+    import torch
+    hq, hkv, d, group, batch, n_ctx, chunk, seed = 32, 8, 128, 4, 8, 1 << 20, 2048, 11
+    mask = synth.retrieval_mask(seed, 1, hkv, 0.5)[0]
+    table = device_table()
+    handle = duo.duo_cache_create(1, batch, hq, hkv, d, SINK, RECENT, n_ctx + chunk, mask[None])
+    try:
+        fill_cache_by_append(duo, handle, table, seed, 0, batch, hkv, d, n_ctx, chunk=1 << 16)
+        q = device_fill(table, seed, 0, synth.TENSOR_Q, batch, n_ctx, chunk, hq, d)
+        k = device_fill(table, seed, 0, synth.TENSOR_K, batch, n_ctx, chunk, hkv, d)
+        v = device_fill(table, seed, 0, synth.TENSOR_V, batch, n_ctx, chunk, hkv, d)
+        out = torch.empty_like(q)
+        duo.duo_attn_prefill(handle, 0, q, k, v, chunk, out)
+        torch.cuda.synchronize()
+        got = from_dev_bits(out[batch - 1])
+    finally:
+        duo.duo_cache_destroy(handle)
+    b = batch - 1
+    positions = np.array([n_ctx, n_ctx + 1, n_ctx + 777, n_ctx + chunk - 1])
+    ret_head = int(np.flatnonzero(mask == 1)[-1])
+    str_head = int(np.flatnonzero(mask == 0)[0])
+    for kvh in (ret_head, str_head):
+        total = n_ctx + chunk
+        if kvh == ret_head:
+            k_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_K, b, total, hkv, d, heads=[kvh]))
+            v_hist = synth.bf16_bits_to_f64(cpu_history_bits(seed, 0, synth.TENSOR_V, b, total, hkv, d, heads=[kvh]))
+        else:
+            # only the rows a streaming head can see are regenerated
+            k_hist = np.zeros((total, 1, d)); v_hist = np.zeros((total, 1, d))
+            for p0, n in ((0, SINK), (n_ctx - RECENT, RECENT + chunk)):
+                k_hist[p0:p0 + n] = synth.bf16_bits_to_f64(synth.counter_bf16(seed, 0, synth.TENSOR_K, b, p0, n, hkv, d, heads=[kvh]))
+                v_hist[p0:p0 + n] = synth.bf16_bits_to_f64(synth.counter_bf16(seed, 0, synth.TENSOR_V, b, p0, n, hkv, d, heads=[kvh]))
+        heads = slice(kvh * group, (kvh + 1) * group)
+        q_bits = np.stack([synth.counter_bf16(seed, 0, synth.TENSOR_Q, b, int(p), 1, hq, d)[0] for p in positions])[:, heads]
+        _oracle_check(q_bits, k_hist, v_hist, positions, mask[kvh:kvh + 1], got[positions - n_ctx][:, heads], None,
+                      "kv head %d of the last sequence" % kvh)
+        del k_hist, v_hist
+
+
 def _long_context_stack(n_ctx, kv_dtype, n_layers, check_layers, seed):
     """Decode one token through a stack of layers whose caches were filled by append alone; the oracle
     checks one retrieval and one streaming KV group of each layer in check_layers."""
