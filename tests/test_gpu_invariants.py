@@ -63,3 +63,32 @@ def test_streaming_heads_cost_the_same_at_any_context_and_retrieval_heads_grow_w
     assert rd_l > 4 * rd_s, (rd_s, rd_l)
     # and a streaming layer is far cheaper than a retrieval layer at long context
     assert sp_l * 10 < rp_l and sd_l * 4 < rd_l
+
+
+@pytest.mark.parametrize("kv_dtype", [0, 1, 2, 3])
+def test_repeated_calls_give_identical_bits(kv_dtype):
+    # the split-K partials are merged in a fixed order by whichever workgroup finishes last, and the
+    # pre-filling kernel has no cross-workgroup accumulation: the same call twice gives the same bits
+    import torch
+    hq, hkv, d, n_ctx = 32, 8, 128, 20000
+    mask = synth.retrieval_mask(5, 1, hkv, 0.5)
+    table = device_table()
+    handle = duo.duo_cache_create(1, 2, hq, hkv, d, SINK, RECENT, n_ctx + 600, mask, kv_dtype)
+    try:
+        fill_cache_by_append(duo, handle, table, 22, 0, 2, hkv, d, n_ctx)
+        q = device_fill(table, 22, 0, synth.TENSOR_Q, 2, n_ctx, 512, hq, d)
+        k = device_fill(table, 22, 0, synth.TENSOR_K, 2, n_ctx, 512, hkv, d)
+        v = device_fill(table, 22, 0, synth.TENSOR_V, 2, n_ctx, 512, hkv, d)
+        outs = []
+        for _ in range(3):
+            o_pre = torch.empty_like(q)
+            lse = torch.empty((2, hq, 512), dtype=torch.float32, device="cuda")
+            duo.duo_attn_prefill(handle, 0, q, k, v, 512, o_pre, lse=lse)
+            o_dec = torch.empty_like(q[:, :1])
+            duo.duo_attn_decode(handle, 0, q[:, :1].contiguous(), o_dec, k=k[:, :1].contiguous(), v=v[:, :1].contiguous())
+            outs.append((o_pre, lse, o_dec))
+        torch.cuda.synchronize()
+        for o_pre, lse, o_dec in outs[1:]:
+            assert torch.equal(o_pre, outs[0][0]) and torch.equal(lse, outs[0][1]) and torch.equal(o_dec, outs[0][2])
+    finally:
+        duo.duo_cache_destroy(handle)
