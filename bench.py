@@ -52,6 +52,12 @@ WORKLOADS = {
                          batch=4, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 4"),
     "c3_decode_b16": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=0, decode=32,
                           batch=16, desc="Llama-3-8B-shaped GQA layer decode at 131072 context, batch 16"),
+    "c2_stack": dict(hq=32, hkv=32, d=128, ratio=0.25, sink=64, recent=256, prefill=32768, chunk=0, decode=16, batch=1,
+                     layers=32, desc="Llama-2-7B-shaped MHA decode at 32768 context through 32 distinct layers "
+                                     "(4.4 GB per token: beyond the memory-side cache), batch 1"),
+    "c3_stack": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=131072, chunk=0, decode=16, batch=1,
+                     layers=32, desc="Llama-3-8B-shaped GQA decode at 131072 context through 32 distinct layers "
+                                     "(8.6 GB per token: beyond the memory-side cache), batch 1"),
     "c4": dict(hq=32, hkv=8, d=128, ratio=0.5, sink=64, recent=256, prefill=1 << 20, chunk=0, decode=4, batch=1,
                layers=32, desc="Llama-3-8B-shaped GQA decode at 1048576 context, 32 layers (attention op only), "
                                "bf16 KV, batch 1"),
