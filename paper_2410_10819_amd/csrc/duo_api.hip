@@ -109,13 +109,14 @@ int choose_splits(const duo_cache* c, const Layer& L, int64_t keys) {
 }
 
 // Rate (bytes per second) at which W workgroups of the even-split decode kernel, one per compute
-// unit, stream bf16 cache rows together: measured on the part at 128K context - about 52 GB/s per
-// workgroup while they are few, 7 TB/s from about 220 workgroups on.
+// unit, stream bf16 cache rows together: measured on the part at 128K context over 32 distinct
+// layers (nothing served from a cache) - about 42 GB/s per workgroup while they are few, 6.5 TB/s
+// from about 220 workgroups on.
 // Quantised rows are bound by a workgroup's instructions before the memory system saturates:
 // about 30 GB/s per workgroup with one code byte per value, 20 GB/s with two codes per byte.
 double decode_stream_rate(int64_t W, int kv_dtype) {
   static const double w_pts[] = {0, 64, 96, 128, 160, 192, 224, 256};
-  static const double r_pts[] = {0, 3.57e12, 5.06e12, 6.2e12, 6.6e12, 6.9e12, 7.0e12, 7.0e12};
+  static const double r_pts[] = {0, 2.84e12, 4.0e12, 5.1e12, 5.7e12, 6.35e12, 6.5e12, 6.6e12};
   double r = r_pts[7];
   if (W < 256) {
     int i = 0;
