@@ -22,13 +22,16 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work; they never synchronise.  One handle must be driven from
  *     one stream at a time.
- *   - The caller owns Q/K/V/out/lse; the library owns the caches and its split-K
- *     scratch, allocated in duo_cache_create - nothing is allocated by append,
- *     prefill or decode (the paper pre-allocates the cache for the whole run,
- *     Section 3.4).
+ *   - The caller owns Q/K/V/out/lse; the library owns the caches, its split-K
+ *     scratch and, for a quantised handle, a bf16 image of one layer's caches that
+ *     pre-filling reads; all of it is allocated in duo_cache_create - nothing is
+ *     allocated by append, prefill or decode (the paper pre-allocates the cache for
+ *     the whole run, Section 3.4).
  *   - Every entry point returns a duo_status_t (0 = ok).  Arguments are validated
- *     before anything is launched; on error nothing has been enqueued and the
- *     handle is unchanged.  duo_last_error() gives a thread-local message.
+ *     before anything is launched; on an argument error nothing has been enqueued
+ *     and the handle is unchanged.  DUO_EHIP reports a failed launch (an earlier
+ *     launch of the same call may then already be enqueued).  duo_last_error()
+ *     gives a thread-local message.
  */
 #ifndef DUOATTN_H
 #define DUOATTN_H
@@ -91,15 +94,17 @@ typedef struct {
 } duo_call_params_t;
 
 /* Allocate both caches of every layer (Section 2.3, Decoding: two KV caches per
- * layer) and the split-K scratch.  DUO_EINVAL for unsupported shapes, DUO_ENOMEM
- * if the device cannot hold the caches. */
+ * layer), the split-K scratch and, when kv_dtype is not DUO_KV_BF16, a bf16 image of
+ * the largest layer's caches for pre-filling (batch * heads * max_seq * head_dim * 2
+ * bytes for K and for V).  DUO_EINVAL for unsupported shapes, DUO_ENOMEM if the
+ * device cannot hold them. */
 int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out);
 int duo_cache_destroy(duo_cache_t* cache);
 /* Forget all tokens of all layers (lengths -> 0).  Cache memory is not cleared. */
 int duo_cache_reset(duo_cache_t* cache);
 /* Tokens appended so far to `layer`, or a negative duo_status_t. */
 int64_t duo_cache_len(const duo_cache_t* cache, int layer);
-/* Bytes of device memory held by the caches (not counting scratch). */
+/* Bytes of device memory held by the caches (not counting scratch and the bf16 image). */
 int64_t duo_cache_bytes(const duo_cache_t* cache);
 
 /* Append n_new tokens to `layer` at positions len .. len+n_new-1
@@ -119,9 +124,9 @@ int duo_kv_append(duo_cache_t* cache, int layer, const void* k, const void* v,
  * the same k, v afterwards.  out: bf16, shape of q.  lse: fp32
  * [batch, n_q_heads, n_new] natural-log-sum-exp of the scaled scores, or NULL.
  * On a quantised cache the cached positions are attended to as the cache holds them
- * (code * scale [+ minimum], rounded to bf16) and the chunk's own positions as given; the
- * first such call allocates a bf16 image of one layer's caches (DUO_ENOMEM if that fails),
- * which the handle keeps, and every call refreshes it from the codes on `stream`. */
+ * (code * scale [+ minimum], rounded to bf16) and the chunk's own positions as given: every
+ * call first brings the handle's bf16 image of this layer up to date from the codes, on
+ * `stream` (only the rows appended since the previous chunk of the same layer). */
 int duo_attn_prefill(duo_cache_t* cache, int layer, const void* q, const void* k,
                      const void* v, int n_new, const duo_call_params_t* params,
                      void* out, float* lse, void* stream);

@@ -45,8 +45,13 @@ struct duo_cache {
   int user_splits = 0;
   bool force_matrix_decode = false;
   int64_t cache_bytes = 0;
-  // bf16 image of one quantised layer's rows for pre-filling (allocated at the first such call)
-  void* deq[4] = {nullptr, nullptr, nullptr, nullptr};   // K retrieval, V retrieval, K streaming, V streaming
+  // bf16 image of one quantised layer's rows for pre-filling (allocated at create for quantised
+  // handles): K retrieval, V retrieval, K streaming, V streaming.  deq_layer / deq_rows say which
+  // layer's retrieval rows the image holds and how many, so that a chunk widens only the rows
+  // appended since the previous chunk of the same layer.
+  void* deq[4] = {nullptr, nullptr, nullptr, nullptr};
+  int deq_layer = -1;
+  int64_t deq_rows = 0;
 };
 
 namespace {
@@ -227,8 +232,8 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   const int hkv = cfg->n_kv_heads, hq = cfg->n_q_heads;
 
   // Per-layer tables (head classes and orders), one device array for all layers.
-  // Layout per layer: head_info[hkv] | ret_heads[hkv] | str_heads[hkv] | q_order[hq]
-  const int per_layer = 3 * hkv + hq;
+  // Layout per layer: head_info[hkv] | ret_heads[hkv] | str_heads[hkv]
+  const int per_layer = 3 * hkv;
   std::vector<int32_t> tables((size_t)per_layer * cfg->n_layers, 0);
   int32_t* d_tables = nullptr;
   hipError_t e = dev_alloc(c, (void**)&d_tables, tables.size() * sizeof(int32_t));
@@ -243,18 +248,11 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
       if (L.mask[h]) { t[h] = (int32_t)(duo::kRetrievalBit | (uint32_t)n_ret); t[hkv + n_ret] = h; ++n_ret; }
       else { t[h] = n_str; t[2 * hkv + n_str] = h; ++n_str; }
     }
-    int qi = 0;
-    for (int pass = 0; pass < 2; ++pass)
-      for (int h = 0; h < hkv; ++h)
-        if ((L.mask[h] != 0) == (pass == 0))
-          for (int g = 0; g < group; ++g) t[3 * hkv + qi++] = h * group + g;
-
     duo::LayerView& v = L.view;
     memset(&v, 0, sizeof(v));
     v.head_info = (const uint32_t*)(d_tables + (size_t)l * per_layer);
     v.ret_heads = d_tables + (size_t)l * per_layer + hkv;
     v.str_heads = d_tables + (size_t)l * per_layer + 2 * hkv;
-    v.q_order = d_tables + (size_t)l * per_layer + 3 * hkv;
     v.n_ret = n_ret; v.n_str = n_str;
     v.batch = cfg->batch; v.n_q_heads = hq; v.n_kv_heads = hkv; v.group = group;
     v.head_dim = cfg->head_dim; v.sink = cfg->sink; v.recent = cfg->recent;
@@ -283,6 +281,26 @@ int duo_cache_create(const duo_config_t* cfg, duo_cache_t** out) {
   e = hipMemcpy(d_tables, tables.data(), tables.size() * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e != hipSuccess) { release(c); return fail_hip(e, "hipMemcpy(tables)"); }
 
+  if (quantised) {
+    // The pre-filling kernel reads bf16 rows: a quantised handle owns a bf16 image of one layer's
+    // caches (the largest layer's), refreshed from the codes by the pre-filling calls.
+    int max_ret = 0, max_str = 0;
+    for (const Layer& x : c->layers) { max_ret = std::max(max_ret, x.view.n_ret); max_str = std::max(max_str, x.view.n_str); }
+    const size_t row = (size_t)cfg->head_dim * 2;
+    const size_t img_ret = (size_t)cfg->batch * max_ret * (size_t)cfg->max_seq * row;
+    const size_t img_str = (size_t)cfg->batch * max_str * (size_t)str_rows * row;
+    const size_t want_img[4] = {img_ret, img_ret, img_str, img_str};
+    for (int i = 0; i < 4; ++i) {
+      e = dev_alloc(c, &c->deq[i], want_img[i]);
+      if (e != hipSuccess) {
+        release(c);
+        return fail(e == hipErrorOutOfMemory ? DUO_ENOMEM : DUO_EHIP,
+                    "hipMalloc of %zu bytes for the bf16 pre-filling image of a quantised layer failed: %s", want_img[i],
+                    hipGetErrorString(e));
+      }
+    }
+  }
+
   c->max_splits = kMaxSplits;
   // split-K scratch: the larger of [batch][q head][split] rows and, for the even-split kernel,
   // (workgroups + segments) rows per query head of a group
@@ -309,6 +327,8 @@ int duo_cache_destroy(duo_cache_t* c) {
 int duo_cache_reset(duo_cache_t* c) {
   if (!c) return fail(DUO_EINVAL, "cache handle is NULL");
   for (auto& L : c->layers) L.len = 0;
+  c->deq_layer = -1;
+  c->deq_rows = 0;
   return DUO_OK;
 }
 
@@ -368,30 +388,17 @@ static int prefill_common(duo_cache_t* c, int layer, const void* q, const void* 
                 (long long)L.len, (long long)c->cfg.max_seq);
   duo::LayerView view = L.view;
   if (c->cfg.kv_dtype != DUO_KV_BF16) {
-    // The pre-filling kernel reads bf16 rows: the rows the layer holds are widened into a scratch
-    // image first (a few bytes of traffic per cached row against the chunk's attention over it),
-    // and the kernel runs on that image; the chunk's own rows are attended to as given.
-    if (!c->deq[0]) {
-      int max_ret = 0, max_str = 0;
-      for (const Layer& x : c->layers) { max_ret = std::max(max_ret, x.view.n_ret); max_str = std::max(max_str, x.view.n_str); }
-      const size_t row = (size_t)c->cfg.head_dim * 2;
-      const size_t ret_bytes = (size_t)c->cfg.batch * max_ret * (size_t)c->cfg.max_seq * row;
-      const size_t str_bytes = (size_t)c->cfg.batch * max_str * ((size_t)c->cfg.sink + c->cfg.recent) * row;
-      const size_t want[4] = {ret_bytes, ret_bytes, str_bytes, str_bytes};
-      for (int i = 0; i < 4; ++i) {
-        hipError_t e = dev_alloc(c, &c->deq[i], want[i]);
-        if (e != hipSuccess) {
-          // what was allocated stays owned by the handle; the next call tries again from the start
-          for (int j = 0; j < 4; ++j) c->deq[j] = nullptr;
-          return fail(e == hipErrorOutOfMemory ? DUO_ENOMEM : DUO_EHIP,
-                      "hipMalloc of %zu bytes for the bf16 image of a quantised layer failed: %s", want[i],
-                      hipGetErrorString(e));
-        }
-      }
-    }
+    // The pre-filling kernel reads bf16 rows: the rows the layer holds are widened into the handle's
+    // bf16 image first (a few bytes of traffic per cached row against the chunk's attention over
+    // it) - of the retrieval rows only those appended since the image last held this layer - and
+    // the kernel runs on that image; the chunk's own rows are attended to as given.
     if (L.len > 0) {
-      hipError_t e = duo::launch_dequant(L.view, L.len, c->deq[0], c->deq[1], c->deq[2], c->deq[3], (hipStream_t)stream);
-      if (e != hipSuccess) return fail_hip(e, "dequantisation launch");
+      const bool same = c->deq_layer == layer && c->deq_rows <= L.len;
+      const int64_t first = same ? c->deq_rows : 0;
+      hipError_t e = duo::launch_dequant(L.view, first, L.len, c->deq[0], c->deq[1], c->deq[2], c->deq[3], (hipStream_t)stream);
+      if (e != hipSuccess) { c->deq_layer = -1; return fail_hip(e, "dequantisation launch"); }
+      c->deq_layer = layer;
+      c->deq_rows = L.len;
     }
     view.k_ret = (uint8_t*)c->deq[0]; view.v_ret = (uint8_t*)c->deq[1];
     view.k_str = (uint8_t*)c->deq[2]; view.v_str = (uint8_t*)c->deq[3];
@@ -484,10 +491,8 @@ static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k
     a.units_ret = (int32_t)std::max<int64_t>(1, (L.len + unit - 1) / unit);
     a.units_str = (int32_t)std::max<int64_t>(1, (rows_str + unit - 1) / unit);
     a.ret_workers = choose_ret_workers(c, L, a.units_ret);
-    e = duo::launch_decode_sk(a, (hipStream_t)stream);
-  } else {
-    e = duo::launch_decode(a, (hipStream_t)stream);
   }
+  e = use_sk ? duo::launch_decode_sk(a, (hipStream_t)stream) : duo::launch_decode(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "decode launch");
   if (commit) L.len += 1;
   return DUO_OK;

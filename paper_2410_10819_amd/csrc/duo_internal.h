@@ -36,7 +36,6 @@ struct LayerView {
   const uint32_t* head_info;  // [n_kv_heads]
   const int32_t* ret_heads;   // [n_ret] KV head index of each retrieval slot
   const int32_t* str_heads;   // [n_str]
-  const int32_t* q_order;     // [n_q_heads] query heads, retrieval groups first
   int32_t n_ret, n_str;
   int32_t batch, n_q_heads, n_kv_heads, group, head_dim;
   int32_t sink, recent;
@@ -104,11 +103,32 @@ hipError_t launch_export(const LayerView& lv, int batch_idx, int kv_head, int64_
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_sk(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
-// Widen the rows a quantised layer holds (cache length len) to bf16 rows in the same layouts:
+// Widen rows a quantised layer holds (cache length len) to bf16 rows in the same layouts:
 // k_ret_out / v_ret_out [batch][n_ret][max_seq][head_dim] and k_str_out / v_str_out
-// [batch][n_str][sink + recent][head_dim], bf16.  Rows beyond the ones held are not written.
-hipError_t launch_dequant(const LayerView& lv, int64_t len, void* k_ret_out, void* v_ret_out, void* k_str_out,
-                          void* v_str_out, hipStream_t stream);
+// [batch][n_str][sink + recent][head_dim], bf16.  Of the retrieval rows only positions
+// first_ret_row .. len-1 are widened (the image already holds the earlier ones); the streaming
+// rows (at most sink + recent per head) are widened whole.  Rows beyond the ones held are not written.
+hipError_t launch_dequant(const LayerView& lv, int64_t first_ret_row, int64_t len, void* k_ret_out, void* v_ret_out,
+                          void* k_str_out, void* v_str_out, hipStream_t stream);
+
+// fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448: the one encoder
+// of the append kernel and of the decode kernels' fused append.
+__device__ inline uint32_t e4m3_encode(float x) {
+  uint32_t u = __float_as_uint(x);
+  const uint32_t sign = (u >> 24) & 0x80u;
+  u &= 0x7FFFFFFFu;
+  const float a = __uint_as_float(u);
+  uint32_t code;
+  if (a >= 448.0f) {
+    code = 0x7Eu;
+  } else if (a < 0.015625f) {             // below the smallest normal 2^-6: grid step 2^-9
+    code = (uint32_t)rintf(a * 512.0f);   // 8 carries into the smallest normal
+  } else {
+    const uint32_t r = u + 0x7FFFFu + ((u >> 20) & 1u);   // RNE to 3 mantissa bits
+    code = (r >> 20) - ((127u - 7u) << 3);
+  }
+  return code | sign;
+}
 
 // Number of rows a streaming cache holds after `len` appends.
 __host__ __device__ inline int64_t streaming_rows(int64_t len, int sink, int recent) {

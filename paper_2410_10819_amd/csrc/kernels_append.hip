@@ -12,24 +12,6 @@
 namespace duo {
 namespace {
 
-// fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448.
-__device__ inline uint32_t e4m3_encode(float x) {
-  uint32_t u = __float_as_uint(x);
-  uint32_t sign = (u >> 24) & 0x80u;
-  u &= 0x7FFFFFFFu;
-  float a = __uint_as_float(u);
-  uint32_t code;
-  if (a >= 448.0f) {
-    code = 0x7Eu;
-  } else if (a < 0.015625f) {             // below the smallest normal 2^-6: grid step 2^-9
-    code = (uint32_t)rintf(a * 512.0f);   // 8 carries into the smallest normal
-  } else {
-    uint32_t r = u + 0x7FFFFu + ((u >> 20) & 1u);   // RNE to 3 mantissa bits
-    code = (r >> 20) - ((127u - 7u) << 3);
-  }
-  return code | sign;
-}
-
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -217,7 +199,7 @@ __global__ __launch_bounds__(256) void export_kernel(LayerView lv, int batch_idx
 
 // bf16 image of quantised rows: value = code * scale (fp8) or code * scale + minimum (int4, int8),
 // in fp32, rounded to nearest even.  One 16-byte piece of output (8 values) per thread; a segment
-// is one (sequence, head) run of `seg_stride` rows of which the first `rows` are widened.
+// is one (sequence, head) run of `seg_stride` rows of which `rows` rows from `first_row` on are widened.
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
   uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
   a += 0x7FFFu + ((a >> 16) & 1u);
@@ -228,13 +210,13 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
 template <int MODE>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes, const float* __restrict__ params,
                                                       uint4* __restrict__ out, int head_dim, int64_t n_seg,
-                                                      int64_t seg_stride, int64_t rows) {
+                                                      int64_t seg_stride, int64_t first_row, int64_t rows) {
   const int ppr = head_dim / 8;   // pieces per row
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= n_seg * rows * ppr) return;
   const int piece = (int)(idx % ppr);
   const int64_t r = idx / ppr;
-  const int64_t row = (r / rows) * seg_stride + r % rows;
+  const int64_t row = (r / rows) * seg_stride + first_row + r % rows;
   float f[8];
   if constexpr (MODE == 2) {
     const uint32_t w = *(const uint32_t*)(codes + row * (head_dim / 2) + piece * 4);
@@ -264,24 +246,26 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
 
 }  // namespace
 
-hipError_t launch_dequant(const LayerView& lv, int64_t len, void* k_ret_out, void* v_ret_out, void* k_str_out,
-                          void* v_str_out, hipStream_t stream) {
+hipError_t launch_dequant(const LayerView& lv, int64_t first_ret_row, int64_t len, void* k_ret_out, void* v_ret_out,
+                          void* k_str_out, void* v_str_out, hipStream_t stream) {
   if (lv.kv_mode < 1 || lv.kv_mode > 3) return hipErrorInvalidValue;
+  if (first_ret_row < 0 || first_ret_row > len) return hipErrorInvalidValue;
   const int64_t cap = (int64_t)lv.sink + lv.recent;
-  struct { const uint8_t* codes; const float* params; void* out; int64_t n_seg, stride, rows; } parts[] = {
-      {lv.k_ret, lv.ks_ret, k_ret_out, (int64_t)lv.batch * lv.n_ret, lv.max_seq, len},
-      {lv.v_ret, lv.vs_ret, v_ret_out, (int64_t)lv.batch * lv.n_ret, lv.max_seq, len},
-      {lv.k_str, lv.ks_str, k_str_out, (int64_t)lv.batch * lv.n_str, cap, streaming_rows(len, lv.sink, lv.recent)},
-      {lv.v_str, lv.vs_str, v_str_out, (int64_t)lv.batch * lv.n_str, cap, streaming_rows(len, lv.sink, lv.recent)}};
+  const int64_t str_rows = streaming_rows(len, lv.sink, lv.recent);
+  struct { const uint8_t* codes; const float* params; void* out; int64_t n_seg, stride, first, rows; } parts[] = {
+      {lv.k_ret, lv.ks_ret, k_ret_out, (int64_t)lv.batch * lv.n_ret, lv.max_seq, first_ret_row, len - first_ret_row},
+      {lv.v_ret, lv.vs_ret, v_ret_out, (int64_t)lv.batch * lv.n_ret, lv.max_seq, first_ret_row, len - first_ret_row},
+      {lv.k_str, lv.ks_str, k_str_out, (int64_t)lv.batch * lv.n_str, cap, 0, str_rows},
+      {lv.v_str, lv.vs_str, v_str_out, (int64_t)lv.batch * lv.n_str, cap, 0, str_rows}};
   for (auto& p : parts) {
     const int64_t pieces = p.n_seg * p.rows * (lv.head_dim / 8);
     if (pieces <= 0) continue;
     if (!p.out) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((pieces + 255) / 256)), block(256);
     uint4* out = (uint4*)p.out;
-    if (lv.kv_mode == 1) dequant_kernel<1><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.rows);
-    else if (lv.kv_mode == 2) dequant_kernel<2><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.rows);
-    else dequant_kernel<3><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.rows);
+    if (lv.kv_mode == 1) dequant_kernel<1><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.first, p.rows);
+    else if (lv.kv_mode == 2) dequant_kernel<2><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.first, p.rows);
+    else dequant_kernel<3><<<grid, block, 0, stream>>>(p.codes, p.params, out, lv.head_dim, p.n_seg, p.stride, p.first, p.rows);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -1,8 +1,8 @@
 // Decode attention on the vector unit: one query per sequence against the split KV
 // cache (paper, Section 2.3, Decoding; attention definitions of Section 2.2).
-// This kernel serves one query head per KV head on a bf16 cache (its templates
-// also cover query groups and fp8 rows, which the matrix-core kernel in
-// kernels_decode_sk.hip handles with far fewer instructions per byte).
+// This kernel serves one query head per KV head on a bf16 cache; query groups and
+// quantised caches go to the matrix-core kernel in kernels_decode_sk.hip, which
+// handles them with far fewer instructions per byte.
 //
 // The step is bound by HBM bandwidth: every cached K and V row of a retrieval
 // head is read once per token, while a streaming head reads at most
@@ -71,24 +71,6 @@ __device__ inline float4 coherent_load4(const float4* p) {
 }
 
 
-// fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448.
-__device__ inline uint32_t e4m3_encode(float x) {
-  uint32_t u = __float_as_uint(x);
-  uint32_t sign = (u >> 24) & 0x80u;
-  u &= 0x7FFFFFFFu;
-  float a = __uint_as_float(u);
-  uint32_t code;
-  if (a >= 448.0f) {
-    code = 0x7Eu;
-  } else if (a < 0.015625f) {
-    code = (uint32_t)rintf(a * 512.0f);
-  } else {
-    uint32_t r = u + 0x7FFFFu + ((u >> 20) & 1u);
-    code = (r >> 20) - ((127u - 7u) << 3);
-  }
-  return code | sign;
-}
-
 // Sum over the LPR adjacent lanes of a row group with DPP cross-lane moves
 // (quad permutes, then half-row and row mirrors: every lane of an already
 // reduced sub-group holds the same value, so a mirror acts as an exchange).
@@ -103,47 +85,19 @@ __device__ inline float group_sum(float x) {
     x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
   return x;
 }
-template <int LPR>
-__device__ inline float group_max(float x) {
-  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)));
-  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)));
-  if constexpr (LPR >= 8)
-    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true)));
-  if constexpr (LPR >= 16)
-    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true)));
-  return x;
+// Widen one 16-byte piece of a row (8 bf16 values) to floats.
+__device__ inline void widen(const uint4& c, float (&f)[8]) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(w[i]); f[2 * i + 1] = bf16_hi(w[i]); }
 }
 
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-
-// Widen one 16-byte piece of a row to floats: 8 bf16 values or 16 E4M3 codes.
-template <bool FP8>
-struct Piece {
-  static constexpr int N = FP8 ? 16 : 8;
-  __device__ static inline void widen(const uint4& c, float (&f)[N]) {
-    const uint32_t w[4] = {c.x, c.y, c.z, c.w};
-    if constexpr (FP8) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
-        f32x2_t b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
-        f[4 * i] = a[0]; f[4 * i + 1] = a[1]; f[4 * i + 2] = b[0]; f[4 * i + 3] = b[1];
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(w[i]); f[2 * i + 1] = bf16_hi(w[i]); }
-    }
-  }
-};
-
-template <int D, int G, bool FP8>
+template <int D>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
-  constexpr int EPL = Piece<FP8>::N;   // elements per lane
-  constexpr int LPR = D / EPL;         // lanes per row
+  constexpr int LPR = D / 8;           // lanes per row (8 bf16 values per lane)
   constexpr int RPL = 64 / LPR;        // rows per wavefront load
   constexpr int RPB = 4 * RPL;         // rows per block iteration (4 wavefronts)
-  // row iterations per register buffer: as many as fit beside the per-head state
-  constexpr int U = (FP8 && G == 2) ? 2 : 4;
+  constexpr int U = 4;                 // row iterations per register buffer
   constexpr int STEP = RPB * U;        // rows per buffer
   const LayerView& lv = a.lv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -155,7 +109,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   int kvh, split = 0, nsplit;
   int64_t j0, j1, exclude = -1, new_row;
   uint8_t *kbase, *vbase;
-  float *ksbase = nullptr, *vsbase = nullptr;
   bool with_new = a.k_new != nullptr;
   if (retrieval) {
     const int slot = blockIdx.x / a.splits;
@@ -170,7 +123,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     const int64_t head_row0 = ((int64_t)b * lv.n_ret + slot) * lv.max_seq;
     kbase = lv.k_ret + head_row0 * lv.row_bytes;
     vbase = lv.v_ret + head_row0 * lv.row_bytes;
-    if (FP8) { ksbase = lv.ks_ret + head_row0; vsbase = lv.vs_ret + head_row0; }
     with_new = with_new && split == nsplit - 1;
     new_row = a.cache_len;
   } else {
@@ -188,10 +140,9 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     const int64_t head_row0 = ((int64_t)b * lv.n_str + slot) * cap;
     kbase = lv.k_str + head_row0 * lv.row_bytes;
     vbase = lv.v_str + head_row0 * lv.row_bytes;
-    if (FP8) { ksbase = lv.ks_str + head_row0; vsbase = lv.vs_str + head_row0; }
   }
 
-  struct Buf { uint4 k[U], v[U]; float ks[U], vs[U]; };
+  struct Buf { uint4 k[U], v[U]; };
   const int row_in_block = wave * RPL + grp;
   // Loads past the item's end are redirected to its last row (row 0 of the head's
   // cache for an empty item: allocated memory whose value is then ignored).
@@ -203,98 +154,66 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
       const int64_t rc = r < j1 ? r : last_row;
       buf.k[u] = stream_load16(kbase + rc * lv.row_bytes + sub * 16);
       buf.v[u] = stream_load16(vbase + rc * lv.row_bytes + sub * 16);
-      if constexpr (FP8) { buf.ks[u] = ksbase[rc]; buf.vs[u] = vsbase[rc]; }
     }
   };
-  // Raw query pieces and the new token's pieces first (they are waited for first),
+  // Raw query piece and the new token's pieces first (they are waited for first),
   // then the first K/V rows; the barrier keeps that issue order.
-  uint4 q_raw[G][EPL / 8];
-  {
-    const uint4* qp = (const uint4*)((const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + (int64_t)kvh * G) * D + sub * EPL);
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int i = 0; i < EPL / 8; ++i) q_raw[g][i] = qp[g * (D / 8) + i];
-  }
-  uint4 new_k[EPL / 8], new_v[EPL / 8];   // the new token's piece: EPL bf16 values
+  const uint4 q_raw = *(const uint4*)((const uint16_t*)a.q + ((int64_t)b * lv.n_q_heads + kvh) * D + sub * 8);
+  uint4 new_k = make_uint4(0, 0, 0, 0), new_v = new_k;   // the new token's piece
   if (with_new) {
-    const uint4* kin = (const uint4*)((const uint16_t*)a.k_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * EPL);
-    const uint4* vin = (const uint4*)((const uint16_t*)a.v_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * EPL);
-#pragma unroll
-    for (int i = 0; i < EPL / 8; ++i) { new_k[i] = kin[i]; new_v[i] = vin[i]; }
+    new_k = *(const uint4*)((const uint16_t*)a.k_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * 8);
+    new_v = *(const uint4*)((const uint16_t*)a.v_new + ((int64_t)b * lv.n_kv_heads + kvh) * D + sub * 8);
   }
   __builtin_amdgcn_sched_barrier(0);
   Buf buf_a;
   issue(buf_a, j0);
   __builtin_amdgcn_sched_barrier(0);
 
-  // Query pieces of the group's heads, pre-multiplied by scale * log2(e).
-  float q[G][EPL];
+  // Query piece, pre-multiplied by scale * log2(e).
+  float q[8];
   {
     const float c = lv.scale * kLog2e;
+    widen(q_raw, q);
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int i = 0; i < EPL / 8; ++i) {
-        float f[8];
-        Piece<false>::widen(q_raw[g][i], f);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) q[g][8 * i + e] = f[e] * c;
-      }
+    for (int e = 0; e < 8; ++e) q[e] *= c;
   }
   __builtin_amdgcn_sched_barrier(0);
-  float m[G], l[G], o[G][EPL];
+  float m = -INFINITY, l = 0.f, o[8];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = -INFINITY; l[g] = 0.f;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) o[g][i] = 0.f;
-  }
+  for (int i = 0; i < 8; ++i) o[i] = 0.f;
 
   auto consume = [&](const Buf& buf, int64_t base) {
-    float s[U][G];
+    float s[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = base + u * RPB + row_in_block;
       const bool ok = r < j1 && r != exclude;
-      float kf[EPL];
-      Piece<FP8>::widen(buf.k[u], kf);
+      float kf[8];
+      widen(buf.k[u], kf);
+      float d = 0.f;
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float d = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) d = fmaf(q[g][i], kf[i], d);
-        d = group_sum<LPR>(d);
-        if constexpr (FP8) d *= buf.ks[u];
-        s[u][g] = ok ? d : -INFINITY;
-      }
+      for (int i = 0; i < 8; ++i) d = fmaf(q[i], kf[i], d);
+      d = group_sum<LPR>(d);
+      s[u] = ok ? d : -INFINITY;
     }
-    float p[U][G];
+    float mn = m;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float mn = m[g];
+    for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u]);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    const float alpha = fast_exp2(m - mu);
+    float p[U], sum = 0.f;
 #pragma unroll
-      for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u][g]);
-      const float mu = mn == -INFINITY ? 0.f : mn;
-      const float alpha = fast_exp2(m[g] - mu);
-      float sum = 0.f;
+    for (int u = 0; u < U; ++u) { p[u] = fast_exp2(s[u] - mu); sum += p[u]; }
+    l = l * alpha + sum;
+    m = mn;
 #pragma unroll
-      for (int u = 0; u < U; ++u) { p[u][g] = fast_exp2(s[u][g] - mu); sum += p[u][g]; }
-      l[g] = l[g] * alpha + sum;
-      m[g] = mn;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) o[g][i] *= alpha;
-    }
+    for (int i = 0; i < 8; ++i) o[i] *= alpha;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float vf[EPL];
-      Piece<FP8>::widen(buf.v[u], vf);
+      float vf[8];
+      widen(buf.v[u], vf);
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float pw = FP8 ? p[u][g] * buf.vs[u] : p[u][g];
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) o[g][i] = fmaf(pw, vf[i], o[g][i]);
-      }
+      for (int i = 0; i < 8; ++i) o[i] = fmaf(p[u], vf[i], o[i]);
     }
   };
 
@@ -302,153 +221,96 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   // current buffer is consumed.  Inside the loop every issue is unconditional (a
   // conditional one would make the compiler's wait counts assume the shorter queue
   // and drain it); the scheduling barriers keep the loads from being sunk below the
-  // arithmetic.  Nothing is loaded past the item's last row.  The variants with the
-  // most per-head state have no registers for a second buffer.
-  constexpr bool kTwoBuffers = !((FP8 && G >= 4) || G >= 8);
+  // arithmetic.  Nothing is loaded past the item's last row.
   if (j0 < j1) {
     int64_t base = j0;
-    if constexpr (kTwoBuffers) {
-      Buf buf_b;
-      while (base + 2 * STEP < j1) {
-        issue(buf_b, base + STEP);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(buf_a, base);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(buf_a, base + 2 * STEP);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(buf_b, base + STEP);
-        __builtin_amdgcn_sched_barrier(0);
-        base += 2 * STEP;
-      }
-      if (base + STEP < j1) {
-        issue(buf_b, base + STEP);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(buf_a, base);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(buf_b, base + STEP);
-      } else {
-        consume(buf_a, base);
-      }
+    Buf buf_b;
+    while (base + 2 * STEP < j1) {
+      issue(buf_b, base + STEP);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(buf_a, base);
+      __builtin_amdgcn_sched_barrier(0);
+      issue(buf_a, base + 2 * STEP);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(buf_b, base + STEP);
+      __builtin_amdgcn_sched_barrier(0);
+      base += 2 * STEP;
+    }
+    if (base + STEP < j1) {
+      issue(buf_b, base + STEP);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(buf_a, base);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(buf_b, base + STEP);
     } else {
       consume(buf_a, base);
-      for (base += STEP; base < j1; base += STEP) {
-        issue(buf_a, base);
-        consume(buf_a, base);
-      }
     }
   }
 
   // The new token, handled by row group 0 of wavefront 0 of the item that owns it;
   // with a.commit its rows are also written into the cache.
   if (with_new && wave == 0 && grp == 0) {
-    float kf[EPL], vf[EPL];
-    float ksc = 1.f, vsc = 1.f;
-    if constexpr (!FP8) {
-      Piece<false>::widen(new_k[0], kf);
-      Piece<false>::widen(new_v[0], vf);
-      if (a.commit) {
-        *(uint4*)(kbase + new_row * lv.row_bytes + sub * 16) = new_k[0];
-        *(uint4*)(vbase + new_row * lv.row_bytes + sub * 16) = new_v[0];
-      }
-    } else {
-      // quantise exactly as the append kernel does, then attend to the dequantised row
-      float kmax = 0.f, vmax = 0.f;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        float f[8];
-        Piece<false>::widen(new_k[i], f);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { kf[8 * i + e] = f[e]; kmax = fmaxf(kmax, fabsf(f[e])); }
-        Piece<false>::widen(new_v[i], f);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { vf[8 * i + e] = f[e]; vmax = fmaxf(vmax, fabsf(f[e])); }
-      }
-      kmax = group_max<LPR>(kmax);
-      vmax = group_max<LPR>(vmax);
-      ksc = kmax == 0.f ? 1.0f : kmax / 448.0f;
-      vsc = vmax == 0.f ? 1.0f : vmax / 448.0f;
-      uint32_t kq[4] = {0, 0, 0, 0}, vq[4] = {0, 0, 0, 0};
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        kq[i / 4] |= e4m3_encode(kf[i] / ksc) << (8 * (i % 4));
-        vq[i / 4] |= e4m3_encode(vf[i] / vsc) << (8 * (i % 4));
-      }
-      const uint4 kc = make_uint4(kq[0], kq[1], kq[2], kq[3]);
-      const uint4 vc = make_uint4(vq[0], vq[1], vq[2], vq[3]);
-      Piece<true>::widen(kc, kf);
-      Piece<true>::widen(vc, vf);
-      if (a.commit) {
-        *(uint4*)(kbase + new_row * lv.row_bytes + sub * 16) = kc;
-        *(uint4*)(vbase + new_row * lv.row_bytes + sub * 16) = vc;
-        if (sub == 0) { ksbase[new_row] = ksc; vsbase[new_row] = vsc; }
-      }
+    float kf[8], vf[8];
+    widen(new_k, kf);
+    widen(new_v, vf);
+    if (a.commit) {
+      *(uint4*)(kbase + new_row * lv.row_bytes + sub * 16) = new_k;
+      *(uint4*)(vbase + new_row * lv.row_bytes + sub * 16) = new_v;
     }
+    float d = 0.f;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float d = 0.f;
+    for (int i = 0; i < 8; ++i) d = fmaf(q[i], kf[i], d);
+    d = group_sum<LPR>(d);
+    const float mn = fmaxf(m, d);
+    const float alpha = fast_exp2(m - mn);
+    const float pw = fast_exp2(d - mn);
+    l = l * alpha + pw;
+    m = mn;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) d = fmaf(q[g][i], kf[i], d);
-      d = group_sum<LPR>(d) * ksc;
-      const float mn = fmaxf(m[g], d);
-      const float alpha = fast_exp2(m[g] - mn);
-      const float pw = fast_exp2(d - mn);
-      l[g] = l[g] * alpha + pw;
-      m[g] = mn;
-      const float pv = pw * vsc;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) o[g][i] = fmaf(pv, vf[i], o[g][i] * alpha);
-    }
+    for (int i = 0; i < 8; ++i) o[i] = fmaf(pw, vf[i], o[i] * alpha);
   }
 
   // Merge the row groups of a wavefront.
 #pragma unroll
   for (int off = LPR; off < 64; off <<= 1) {
+    const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+    const float mn = fmaxf(m, mo);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    const float a1 = fast_exp2(m - mu), a2 = fast_exp2(mo - mu);
+    l = l * a1 + lo * a2;
+    m = mn;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float mo = __shfl_xor(m[g], off), lo = __shfl_xor(l[g], off);
-      const float mn = fmaxf(m[g], mo);
-      const float mu = mn == -INFINITY ? 0.f : mn;
-      const float a1 = fast_exp2(m[g] - mu), a2 = fast_exp2(mo - mu);
-      l[g] = l[g] * a1 + lo * a2;
-      m[g] = mn;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) o[g][i] = o[g][i] * a1 + __shfl_xor(o[g][i], off) * a2;
-    }
+    for (int i = 0; i < 8; ++i) o[i] = o[i] * a1 + __shfl_xor(o[i], off) * a2;
   }
   // Merge the four wavefronts through LDS.
-  constexpr int kSmO = 4 * G * D > 1024 ? 4 * G * D : 1024;
-  __shared__ float sm_o[kSmO];   // [wave][g][d] during the wavefront merge, [part][d] in the split merge
-  __shared__ float sm_m[4][G], sm_l[4][G];
+  __shared__ float sm_o[1024];   // [wave][d] during the wavefront merge, [slot][d] in the split merge
+  __shared__ float sm_m[4], sm_l[4];
   __shared__ float sm_m2[16], sm_l2[16];   // per merge slot, in the split merge
   __shared__ int sm_last;
   if (grp == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) sm_o[(wave * G + g) * D + sub * EPL + i] = o[g][i];
-      if (sub == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
-    }
+    for (int i = 0; i < 8; ++i) sm_o[wave * D + sub * 8 + i] = o[i];
+    if (sub == 0) { sm_m[wave] = m; sm_l[wave] = l; }
   }
   __syncthreads();
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int g = idx / D, d = idx % D;
+  if (tid < D) {
+    const int d = tid;
     float mn = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) mn = fmaxf(mn, sm_m[w][g]);
+    for (int w = 0; w < 4; ++w) mn = fmaxf(mn, sm_m[w]);
     const float mu = mn == -INFINITY ? 0.f : mn;
     float acc = 0.f, ls = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float wgt = fast_exp2(sm_m[w][g] - mu);
-      acc += wgt * sm_o[(w * G + g) * D + d];
-      ls += wgt * sm_l[w][g];
+      const float wgt = fast_exp2(sm_m[w] - mu);
+      acc += wgt * sm_o[w * D + d];
+      ls += wgt * sm_l[w];
     }
-    const int h = kvh * G + g;
     if (nsplit == 1) {
-      ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + h) * D + d] = f32_to_bf16(acc / ls);
-      if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + h] = (mn + log2f(ls)) * kLn2;
+      ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + kvh) * D + d] = f32_to_bf16(acc / ls);
+      if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + kvh] = (mn + log2f(ls)) * kLn2;
     } else {
-      const int64_t pi = ((int64_t)b * lv.n_q_heads + h) * nsplit + split;
+      const int64_t pi = ((int64_t)b * lv.n_q_heads + kvh) * nsplit + split;
       coherent_store(a.part_o + pi * D + d, acc);
       if (d == 0) { coherent_store(a.part_ml + pi * 2, mn); coherent_store(a.part_ml + pi * 2 + 1, ls); }
     }
@@ -456,10 +318,14 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   if (nsplit == 1) return;
 
   // Ticket: the last item of this (sequence, KV head) to get here merges the partials.
-  // The partials are written and read with device-scope atomic accesses, which go
-  // to the memory side of the per-XCD L2 caches; waiting for the stores to be
-  // acknowledged before taking the ticket orders them without a cache write-back
-  // (a device-scope fence per workgroup costs about a microsecond each here).
+  // Hand-off protocol (the same in the matrix-core kernel): the partials are written with
+  // device-scope stores, which go through to the memory side of the per-die L2 caches; every
+  // thread waits until its stores are acknowledged (s_waitcnt 0), the workgroup barrier collects
+  // those waits, and only then does one thread take the ticket, so whoever sees the final ticket
+  // value finds every partial in memory.  The compiler fences keep the three steps in that order
+  // in the instruction stream.  (A device-scope release fence per workgroup would add a write-back
+  // of the die's L2, about a microsecond each here, for data that is already written through.)
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   if (tid == 0) {
@@ -470,33 +336,30 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   }
   __syncthreads();
   if (!sm_last) return;
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   // The partials are read with device-scope loads (after the ticket, on which this branch
-  // depends), so no cached copy of an earlier launch's partials can be hit.
-  // All heads of the group at once, one memory round trip: the 256 threads form
-  // SLOTS rows of TPR threads (one float4 of a partial row each); head g owns NP
-  // consecutive slots, slot `part` of a head sums the partials part, part + NP, ...
-  // in that order with a running maximum, and the NP slot results are merged
-  // through LDS in slot order - a fixed order, so the result is deterministic.
+  // depends): they are served from the memory side of the L2 caches, so no stale cached copy
+  // (of an earlier launch's partials, say) can be hit and no cache invalidation is needed.
+  // One memory round trip: the 256 threads form SLOTS rows of TPR threads (one float4 of a
+  // partial row each); slot `part` sums the partials part, part + SLOTS, ... in that order with
+  // a running maximum, and the slot results are merged through LDS in slot order - a fixed
+  // order, so the result is deterministic.
   constexpr int TPR = D / 4;
   constexpr int SLOTS = 256 / TPR;
-  static_assert(SLOTS % G == 0, "group size must divide the merge slots");
-  constexpr int NP = SLOTS / G;
-  const int dq = tid % TPR, slot_id = tid / TPR;
-  const int mg = slot_id / NP, part = slot_id % NP;
+  const int dq = tid % TPR, part = tid / TPR;
   {
-    const int h = kvh * G + mg;
-    const int64_t p0 = ((int64_t)b * lv.n_q_heads + h) * nsplit;
+    const int64_t p0 = ((int64_t)b * lv.n_q_heads + kvh) * nsplit;
     const float2* ml = (const float2*)a.part_ml + p0;
     const float4* po = (const float4*)(a.part_o + p0 * D) + dq;
     float mr = -INFINITY, lr = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     constexpr int B4 = 4;   // partial rows fetched together
-    for (int s0 = part; s0 < nsplit; s0 += NP * B4) {
+    for (int s0 = part; s0 < nsplit; s0 += SLOTS * B4) {
       float2 mlv[B4];
       float4 x[B4];
 #pragma unroll
       for (int j = 0; j < B4; ++j) {
-        const int sidx = s0 + j * NP;
+        const int sidx = s0 + j * SLOTS;
         const int sc = sidx < nsplit ? sidx : nsplit - 1;
         mlv[j] = coherent_load2(ml + sc);
         x[j] = coherent_load4(po + (int64_t)sc * TPR);
@@ -505,7 +368,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
       for (int j = 0; j < B4; ++j) {
         // rows past the end count as empty; decided here, after every load of the batch has
         // been issued, so that no load waits for the one before it
-        const bool there = s0 + j * NP < nsplit;
+        const bool there = s0 + j * SLOTS < nsplit;
         const float mj = there ? mlv[j].x : -INFINITY, lj = there ? mlv[j].y : 0.f;
         const float mn = fmaxf(mr, mj);
         const float mu = mn == -INFINITY ? 0.f : mn;
@@ -517,25 +380,24 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
       }
     }
     __syncthreads();   // sm_o / sm_m / sm_l are free again
-    *(float4*)(sm_o + slot_id * D + 4 * dq) = acc;
-    if (dq == 0) { sm_m2[slot_id] = mr; sm_l2[slot_id] = lr; }
+    *(float4*)(sm_o + part * D + 4 * dq) = acc;
+    if (dq == 0) { sm_m2[part] = mr; sm_l2[part] = lr; }
   }
   __syncthreads();
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int g = idx / D, d = idx % D;
+  if (tid < D) {
+    const int d = tid;
     float mn = -INFINITY;
 #pragma unroll
-    for (int pp = 0; pp < NP; ++pp) mn = fmaxf(mn, sm_m2[g * NP + pp]);
+    for (int pp = 0; pp < SLOTS; ++pp) mn = fmaxf(mn, sm_m2[pp]);
     float tot = 0.f, ls = 0.f;
 #pragma unroll
-    for (int pp = 0; pp < NP; ++pp) {
-      const float wgt = fast_exp2(sm_m2[g * NP + pp] - mn);
-      tot += wgt * sm_o[(g * NP + pp) * D + d];
-      ls += wgt * sm_l2[g * NP + pp];
+    for (int pp = 0; pp < SLOTS; ++pp) {
+      const float wgt = fast_exp2(sm_m2[pp] - mn);
+      tot += wgt * sm_o[pp * D + d];
+      ls += wgt * sm_l2[pp];
     }
-    const int h = kvh * G + g;
-    ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + h) * D + d] = f32_to_bf16(tot / ls);
-    if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + h] = (mn + log2f(ls)) * kLn2;
+    ((uint16_t*)a.out)[((int64_t)b * lv.n_q_heads + kvh) * D + d] = f32_to_bf16(tot / ls);
+    if (a.lse && d == 0) a.lse[(int64_t)b * lv.n_q_heads + kvh] = (mn + log2f(ls)) * kLn2;
   }
 }
 
@@ -548,8 +410,8 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
   if (lv.group != 1 || lv.kv_mode != 0) return hipErrorInvalidValue;
   if (a.splits < 1 || a.splits > kMaxDecodeSplits) return hipErrorInvalidValue;
   dim3 grid(lv.n_ret * a.splits + lv.n_str, lv.batch);
-  if (lv.head_dim == 128) decode_kernel<128, 1, false><<<grid, 256, 0, stream>>>(a);
-  else decode_kernel<64, 1, false><<<grid, 256, 0, stream>>>(a);
+  if (lv.head_dim == 128) decode_kernel<128><<<grid, 256, 0, stream>>>(a);
+  else decode_kernel<64><<<grid, 256, 0, stream>>>(a);
   return hipGetLastError();
 }
 

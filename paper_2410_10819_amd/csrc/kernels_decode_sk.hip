@@ -92,24 +92,6 @@ __device__ inline void coherent_store(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// fp32 -> OCP E4M3 (finite-only) code, round to nearest even, saturating at 448.
-__device__ inline uint32_t e4m3_encode(float x) {
-  uint32_t u = __float_as_uint(x);
-  uint32_t sign = (u >> 24) & 0x80u;
-  u &= 0x7FFFFFFFu;
-  float a = __uint_as_float(u);
-  uint32_t code;
-  if (a >= 448.0f) {
-    code = 0x7Eu;
-  } else if (a < 0.015625f) {
-    code = (uint32_t)rintf(a * 512.0f);
-  } else {
-    uint32_t r = u + 0x7FFFFu + ((u >> 20) & 1u);
-    code = (r >> 20) - ((127u - 7u) << 3);
-  }
-  return code | sign;
-}
-
 // Four E4M3 codes (one dword) -> four bf16 values (two dwords); exact (every E4M3 value has at
 // most 4 significant bits).  The scaled conversion of this architecture turns two codes into a
 // bf16 pair in one instruction; with a scale of one it gives, for every code, the bits of the
@@ -814,9 +796,15 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
       }
     }
     if (n_parts > 1) {
-      // Ticket: the last workgroup of this segment to get here merges the partials.  They are
-      // written and read with device-scope accesses; waiting for the stores to be acknowledged
-      // before taking the ticket orders them without a cache write-back.
+      // Ticket: the last workgroup of this segment to get here merges the partials.  Hand-off
+      // protocol (the same in the vector-unit kernel): the partials are written with device-scope
+      // stores, which go through to the memory side of the per-die L2 caches; every thread waits
+      // until its stores are acknowledged (s_waitcnt 0), the workgroup barrier collects those
+      // waits, and only then does one thread take the ticket, so whoever sees the final ticket
+      // value finds every partial in memory.  The compiler fences keep the steps in that order in
+      // the instruction stream.  (A device-scope release fence per workgroup would add a
+      // write-back of the die's L2 for data that is already written through.)
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
       if (tid == 0) {
@@ -827,8 +815,11 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
       }
       __syncthreads();
       if (sm_last) {
-        // Acquire, then plain 16-byte loads: with dozens of partial rows per head the merge is bound
-        // by what one compute unit can fetch, and device-scope loads (8 bytes at most) were slower.
+        // Reader side: an acquire fence (invalidates this compute unit's and die's cached copies,
+        // e.g. of an earlier launch's partials), then plain 16-byte loads: with dozens of partial
+        // rows per head the merge is bound by what one compute unit can fetch, and device-scope
+        // loads (8 bytes at most), which the vector-unit kernel uses for its few rows, were slower.
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         // All heads of the group at once: 256 threads = SLOTS rows of TPR threads (one float4 of a
         // partial row each); head g owns NP consecutive slots; slot `part` of a head folds the

@@ -379,22 +379,29 @@ def test_prefill_over_a_quantised_cache(hq, hkv, d, sink, recent, chunks, batch,
     q, k, v = make_qkv(77 + kv_dtype, batch, total + n_decode, hq, hkv, d)
     out, lse, handle = run_scenario(duo, cfg, q, k, v, chunks, n_decode, deployed=deployed, fused_decode="step")
     duo.duo_cache_destroy(handle)
-    from helpers import oracle_kv
+    from helpers import ATOL_LSE_IMAGE, oracle_kv
     for b in range(batch):
-        kq, vq = oracle_kv(k[b], v[b], kv_dtype)          # every position through the codec
-        # pre-filling reads the cached rows from a bf16 image of code * scale (+ minimum)
-        kq, vq = (synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(x.astype(np.float32))) for x in (kq, vq))
+        kq, vq = oracle_kv(k[b], v[b], kv_dtype)          # every position through the codec, float64
+        # the library's pre-filling reads the cached rows from a bf16 image of these values
+        ki, vi = (synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(x.astype(np.float32))) for x in (kq, vq))
         kf, vf = synth.bf16_bits_to_f64(k[b]), synth.bf16_bits_to_f64(v[b])
         p0 = 0
         for n in chunks:
-            k_hist = np.concatenate([kq[:p0], kf[p0:p0 + n]])
-            v_hist = np.concatenate([vq[:p0], vf[p0:p0 + n]])
             pos = np.arange(p0, p0 + n)
-            want_o, want_lse = oracle.attention_rows(synth.bf16_bits_to_f64(q[b][pos]), k_hist, v_hist, pos, mask, sink,
-                                                     recent, None,
-                                                     chunk_starts=np.full(n, p0) if deployed else None)
+            qf = synth.bf16_bits_to_f64(q[b][pos])
+            starts = np.full(n, p0) if deployed else None
+            # the definition: float64 attention over the codec's exact output for the cached positions
+            want_o, want_lse = oracle.attention_rows(qf, np.concatenate([kq[:p0], kf[p0:p0 + n]]),
+                                                     np.concatenate([vq[:p0], vf[p0:p0 + n]]), pos, mask, sink,
+                                                     recent, None, chunk_starts=starts)
             assert_close(synth.bf16_bits_to_f64(out[b][pos]), want_o, "chunk at %d, batch %d" % (p0, b))
-            assert np.abs(lse[b][:, pos] - want_lse).max() <= ATOL_LSE
+            assert np.abs(lse[b][:, pos] - want_lse).max() <= ATOL_LSE_IMAGE
+            # secondary, tighter: against the same attention over the bf16-rounded image the kernel reads
+            img_o, img_lse = oracle.attention_rows(qf, np.concatenate([ki[:p0], kf[p0:p0 + n]]),
+                                                   np.concatenate([vi[:p0], vf[p0:p0 + n]]), pos, mask, sink,
+                                                   recent, None, chunk_starts=starts)
+            assert_close(synth.bf16_bits_to_f64(out[b][pos]), img_o, "chunk at %d, batch %d (image)" % (p0, b))
+            assert np.abs(lse[b][:, pos] - img_lse).max() <= ATOL_LSE
             p0 += n
         want_d, _ = oracle_rows(cfg, q, k, v, np.arange(total, total + n_decode), b)
         assert_close(synth.bf16_bits_to_f64(out[b][total:]), want_d, "decode after the quantised prefill")

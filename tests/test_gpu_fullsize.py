@@ -93,7 +93,7 @@ def test_llama3_8b_shape_128k_prefill_32k_chunks():
 
 def test_llama3_8b_shape_128k_prefill_32k_chunks_over_an_int4_cache():
     # the same pre-filling with the cache in 4-bit codes: cached positions are seen as the cache holds them
-    # (bf16 image of code * scale + minimum), the chunk's own positions as given; sampled rows per chunk
+    # (code * scale + minimum), the chunk's own positions as given; sampled rows per chunk
     import torch
     hq, hkv, d, n_ctx, chunk, seed = 32, 8, 128, 131072, 32768, 9
     mask = synth.retrieval_mask(seed, 1, hkv, 0.5)[0]
@@ -114,8 +114,9 @@ def test_llama3_8b_shape_128k_prefill_32k_chunks_over_an_int4_cache():
     rng = np.random.default_rng(seed)
     kb = cpu_history_bits(seed, 0, synth.TENSOR_K, 0, n_ctx, hkv, d)
     vb = cpu_history_bits(seed, 0, synth.TENSOR_V, 0, n_ctx, hkv, d)
-    image = lambda bits: synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(oracle_history_f64(bits, 2).astype(np.float32)))
-    kq, vq = image(kb), image(vb)
+    # the definition: float64 attention over the codec's exact output for the cached positions (the
+    # library reads them from a bf16 image of it; that rounding is inside the tolerance)
+    kq, vq = oracle_history_f64(kb, 2), oracle_history_f64(vb, 2)
     for p in range(0, n_ctx, chunk):
         positions = np.array(_sample_positions(rng, p, chunk, 2))
         k_hist = np.concatenate([kq[:p], synth.bf16_bits_to_f64(kb[p:p + chunk])])
@@ -252,20 +253,20 @@ def _long_context_stack(n_ctx, kv_dtype, n_layers, check_layers, seed):
 
 
 def test_llama3_8b_shape_decode_at_1m_context_32_layers_bf16():
-    _long_context_stack(1 << 20, duo.DUO_KV_BF16, 32, check_layers=(0, 31), seed=4)
+    _long_context_stack(1 << 20, duo.DUO_KV_BF16, 32, check_layers=(0, 16, 31), seed=4)
 
 
 def test_llama3_8b_shape_decode_at_3300000_context_32_layers_fp8():
-    _long_context_stack(3300000, duo.DUO_KV_FP8_E4M3, 32, check_layers=(17,), seed=5)
+    _long_context_stack(3300000, duo.DUO_KV_FP8_E4M3, 32, check_layers=(0, 16, 31), seed=5)
 
 
 def test_llama3_8b_shape_decode_at_3300000_context_32_layers_int4():
     # the paper's capacity setting (Section 3.4: 3.3 million tokens with a 4-bit KV cache) at its shape
-    _long_context_stack(3300000, duo.DUO_KV_INT4, 32, check_layers=(9,), seed=6)
+    _long_context_stack(3300000, duo.DUO_KV_INT4, 32, check_layers=(0, 16, 31), seed=6)
 
 
 def test_llama3_8b_shape_decode_at_2m_context_32_layers_int8():
-    _long_context_stack(1 << 21, duo.DUO_KV_INT8, 32, check_layers=(23,), seed=7)
+    _long_context_stack(1 << 21, duo.DUO_KV_INT8, 32, check_layers=(0, 16, 31), seed=7)
 
 
 @pytest.mark.parametrize("hq,hkv,block", [(32, 8, 128), (32, 32, 0)])
