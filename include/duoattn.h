@@ -173,6 +173,24 @@ int duo_attn_decode(duo_cache_t* cache, int layer, const void* q, const void* k,
                     const void* v, const duo_call_params_t* params, void* out,
                     float* lse, void* stream);
 
+/* duo_attn_decode for callers that must not allocate device memory and want no buffer of the
+ * handle's touched behind their back: code recorded into a HIP graph, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, result and errors as duo_attn_decode, but the
+ * split-K scratch (partial rows and merge tickets) is a fixed array inside the library, present on
+ * every GPU from the moment the library is loaded, instead of the handle's allocation.  The call
+ * allocates and frees nothing and synchronises nothing; it enqueues one small kernel that zeroes
+ * the tickets, then the decode kernel.
+ * Limits: the array holds 4096 partial rows of 128 floats with their (max, sum) pairs (2.1 MB)
+ * and 4096 tickets.  A step needs (workgroups sharing retrieval rows + batch * n_kv_heads) *
+ * group size rows (at most (1024 + batch * n_kv_heads) * group size), or batch * n_q_heads * key
+ * splits rows for one query head per KV head on a bf16 cache, and batch * n_kv_heads tickets;
+ * DUO_ERANGE, with the numbers in duo_last_error(), if that does not fit.
+ * The array is shared by every call on the same GPU and keeps the previous call's contents:
+ * calls that overlap in time on one GPU (two streams, two handles) race - serialise them. */
+int duo_attn_decode_static(duo_cache_t* cache, int layer, const void* q, const void* k,
+                           const void* v, const duo_call_params_t* params, void* out,
+                           float* lse, void* stream);
+
 /* duo_kv_append(n_new = 1) followed by duo_attn_decode(k = v = NULL), as ONE
  * launch: the new token's rows are written into both caches (the length grows
  * by one) while its query attends to the cache plus the new token.  k and v are

@@ -68,6 +68,7 @@ def load() -> ctypes.CDLL:
     lib.duo_attn_gate_mixed.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float), i32, vp, vp, vp]
     lib.duo_attn_decode.argtypes = [vp, i32, vp, vp, vp, ctypes.POINTER(duo_call_params_t), vp, vp, vp]
     lib.duo_decode_step.argtypes = lib.duo_attn_decode.argtypes
+    lib.duo_attn_decode_static.argtypes = lib.duo_attn_decode.argtypes
     lib.duo_cache_export.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, ctypes.POINTER(i64), vp]
     _lib = lib
     return lib
@@ -213,6 +214,14 @@ def duo_attn_decode(cache, layer, q, out, k=None, v=None, lse=None, params=None,
     _check(load().duo_attn_decode(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
                                   _ptr(v, "v", torch.bfloat16), pp, _ptr(out, "out", torch.bfloat16),
                                   _ptr(lse, "lse", torch.float32), _stream(stream)))
+
+
+def duo_attn_decode_static(cache, layer, q, out, k=None, v=None, lse=None, params=None, stream=None):
+    import torch
+    pp, keep = _params(params)
+    _check(load().duo_attn_decode_static(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),
+                                         _ptr(v, "v", torch.bfloat16), pp, _ptr(out, "out", torch.bfloat16),
+                                         _ptr(lse, "lse", torch.float32), _stream(stream)))
 
 
 def duo_decode_step(cache, layer, q, k, v, out, lse=None, params=None, stream=None):

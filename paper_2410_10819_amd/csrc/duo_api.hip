@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -54,7 +55,46 @@ struct duo_cache {
   int64_t deq_rows = 0;
 };
 
+// Split-K scratch of duo_attn_decode_static: partial rows (unnormalised output, then (max, sum)
+// pairs) and the merge tickets, in device memory that exists from the moment the library is loaded
+// until the process ends, one copy per GPU.
+constexpr int kStaticRows = 4096;      // partial rows (one per (workgroup, query head) pair that is split)
+constexpr int kStaticTickets = 4096;   // (sequence, KV head) pairs
+constexpr int kStaticHeadDim = 128;
+constexpr size_t kStaticPartO = (size_t)kStaticRows * kStaticHeadDim * sizeof(float);
+constexpr size_t kStaticPartMl = (size_t)kStaticRows * 2 * sizeof(float);
+constexpr size_t kStaticBytes = kStaticPartO + kStaticPartMl + (size_t)kStaticTickets * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
 namespace {
+
+// The array's address on each device, asked of the runtime once per device (the array's name is
+// only a host-side stand-in; every use below goes through these pointers).
+constexpr int kMaxDevices = 64;
+void* g_static_ptr[kMaxDevices] = {};
+std::mutex g_static_mu;
+
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(DUO_ERANGE, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail_hip(e, "hipGetSymbolAddress(static split-K scratch)");
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return DUO_OK;
+}
+
+// Zero n ints (a kernel, not hipMemsetAsync: the call may be recorded into a graph).
+__global__ void clear_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
 
 constexpr int kMaxSplits = duo::kMaxDecodeSplits;
 
@@ -465,7 +505,8 @@ int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k,
 }
 
 static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
-                         const duo_call_params_t* params, void* out, float* lse, void* stream, bool commit) {
+                         const duo_call_params_t* params, void* out, float* lse, void* stream, bool commit,
+                         bool static_scratch_call = false) {
   int rc = check_handle_layer(c, layer);
   if (rc != DUO_OK) return rc;
   if (!q || !out) return fail(DUO_EINVAL, "q and out must not be NULL");
@@ -492,6 +533,27 @@ static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k
     a.units_str = (int32_t)std::max<int64_t>(1, (rows_str + unit - 1) / unit);
     a.ret_workers = choose_ret_workers(c, L, a.units_ret);
   }
+  if (static_scratch_call) {
+    // the scratch this launch will index: partial rows [0, rows) and tickets [0, n_tickets)
+    const int64_t n_tickets = (int64_t)c->cfg.batch * c->cfg.n_kv_heads;
+    const int64_t rows = use_sk ? ((int64_t)a.ret_workers + n_tickets) * L.view.group
+                                : (int64_t)c->cfg.batch * c->cfg.n_q_heads * a.splits;
+    if (rows > kStaticRows || n_tickets > kStaticTickets || c->cfg.head_dim > kStaticHeadDim)
+      return fail(DUO_ERANGE,
+                  "duo_attn_decode_static: this step needs %lld partial rows and %lld tickets; the static scratch "
+                  "holds %d rows of %d floats and %d tickets (use duo_attn_decode)",
+                  (long long)rows, (long long)n_tickets, kStaticRows, kStaticHeadDim, kStaticTickets);
+    void* base = nullptr;
+    if ((rc = static_scratch(&base)) != DUO_OK) return rc;
+    a.part_o = (float*)base;
+    a.part_ml = (float*)((unsigned char*)base + kStaticPartO);
+    a.tickets = (int32_t*)((unsigned char*)base + kStaticPartO + kStaticPartMl);
+    // every call on this GPU shares the array, which keeps what the last call left: the tickets
+    // must start at zero (the partial rows are written before they are read)
+    clear_i32_kernel<<<dim3((unsigned)((n_tickets + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(a.tickets, (int)n_tickets);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "ticket clear launch");
+  }
   e = use_sk ? duo::launch_decode_sk(a, (hipStream_t)stream) : duo::launch_decode(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "decode launch");
   if (commit) L.len += 1;
@@ -501,6 +563,11 @@ static int decode_common(duo_cache_t* c, int layer, const void* q, const void* k
 int duo_attn_decode(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
                     const duo_call_params_t* params, void* out, float* lse, void* stream) {
   return decode_common(c, layer, q, k, v, params, out, lse, stream, false);
+}
+
+int duo_attn_decode_static(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
+                           const duo_call_params_t* params, void* out, float* lse, void* stream) {
+  return decode_common(c, layer, q, k, v, params, out, lse, stream, false, true);
 }
 
 int duo_decode_step(duo_cache_t* c, int layer, const void* q, const void* k, const void* v,
