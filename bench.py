@@ -1,15 +1,20 @@
 #!/usr/bin/env python3
-"""Benchmark of the DuoAttention hot path on one MI355X.
+"""Benchmark of the DuoAttention hot path on one MI355X.  Prints ONE JSON line.
 
-Default workload (the configuration the headline metric is quoted on): a
-Llama-2-7B-shaped MHA layer - 32 query/KV heads, head_dim 128, 25 % retrieval
-heads (seeded), 64 sink + 256 recent tokens, batch 1.  One "step" is one pass of
-the whole path: reset the cache, pre-fill 32 768 tokens in 4 096-token chunks
-(attention + append per chunk), then 256 decoding steps (append + attention).
-All inputs are synthetic bf16 N(0,1) tensors generated on the device before the
-timed region.  Prints ONE JSON line.
+Default (no --workload): the suite.  The headline - `value`, `config`, `roofline`, `cpu_baseline`, and the
+K steps that --steps / --warmup count - is the largest single-GPU decode configuration: a
+Llama-3-8B-shaped stack of 32 attention layers (32 query / 8 KV heads x 128, half of the KV heads
+retrieval per layer, 64 sink + 256 recent tokens) decoding at 3 300 000 tokens of context over an fp8
+E4M3 KV cache with per-row fp32 scales (111.5 GB).  One "step" is one pass of the whole decode path over
+one batch of synthetic input: 4 new tokens, each through all 32 layers (append to both caches + attention
+over them, one launch per token and layer).  After it the other configurations run as short timed loops
+of their own and are reported under `sub` (the 1M-token bf16 stack, the 3.3M-token 4-bit stack, the
+128K-context GQA layer at batch 1 / 4 / 16 and through 32 distinct layers, the 32K-context MHA layer with
+its chunked pre-filling and through 32 distinct layers), and `roofline_prefill` is the 128K-token
+pre-filling in 32K-token chunks.  All inputs are synthetic bf16 N(0,1) tensors generated on the device
+before the timed regions.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]     (one workload alone, e.g. under rocprofv3)
 """
 from __future__ import annotations
 
@@ -24,8 +29,9 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, scaled by a 1 GiB
-# device copy (summaries under profiles/); known for these workloads only.
+# HBM bytes per launch RECORDED from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --workload NAME`,
+# scaled by a 1 GiB device copy (summaries under profiles/): constants of the build they were taken on, not
+# measured by the run that prints them; known for these workloads only.
 MEASURED_TRAFFIC = {"c2": {"decode": 139.15e6 + 0.17e6, "prefill": 170.2e6 + 33.6e6},
                     "c3_prefill": {"prefill": 2527.9e6 + 268.7e6},
                     "c3_decode_b1": {"decode": 270.26e6 + 0.54e6},
@@ -78,12 +84,18 @@ def visible_pairs(pos0, n, sink, recent, retrieval):
     return int(np.minimum(i + 1, sink + recent).sum())
 
 
+# the suite: (workload, steps, warmup) of the short loops reported under "sub"
+HEADLINE = "c5"
+SUITE = [("c4", 3, 1), ("c6", 3, 1), ("c3_prefill", 3, 1), ("c3_decode_b1", 5, 2), ("c3_decode_b4", 5, 2),
+         ("c3_decode_b16", 5, 2), ("c3_stack", 5, 2), ("c2", 10, 2), ("c2_stack", 5, 2)]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="suite", choices=["suite"] + sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--splits", type=int, default=0, help="key splits per retrieval head in decode (0 = automatic)")
@@ -110,7 +122,30 @@ def main():
     if args.sweep:
         run_sweep(args.sweep, torch, duo, synth, lib, args.seed)
         return
-    w = WORKLOADS[args.workload]
+    if args.workload != "suite":
+        print(json.dumps(run_workload(args.workload, args, torch, duo, synth, lib, not args.no_cpu_baseline)))
+        return
+    result = run_workload(HEADLINE, args, torch, duo, synth, lib, not args.no_cpu_baseline)
+    print("bench: headline %s done" % HEADLINE, file=sys.stderr, flush=True)
+    sub = {}
+    for name, steps, warmup in SUITE:
+        sub_args = argparse.Namespace(**vars(args))
+        sub_args.steps, sub_args.warmup = steps, warmup
+        r = run_workload(name, sub_args, torch, duo, synth, lib, False)
+        sub[name] = {"workload": r["config"]["workload"], "steps": steps, "warmup": warmup,
+                     "ms_per_step": r["ms_per_step"], "dtype": r["dtype"],
+                     "decode_us_per_token": r["value"] if r["unit"] == "us/token" else None,
+                     "roofline_decode": r["roofline_decode"], "roofline_prefill": r["roofline_prefill"]}
+        print("bench: %s done" % name, file=sys.stderr, flush=True)
+    result["roofline_prefill"] = sub["c3_prefill"]["roofline_prefill"]
+    result["prefill_tflops"] = result["roofline_prefill"]["achieved"]
+    result["sub"] = sub
+    print(json.dumps(result))
+
+
+def run_workload(workload, args, torch, duo, synth, lib, with_cpu_baseline):
+    """Time one workload: args.warmup untimed steps, then exactly args.steps timed steps; returns its record."""
+    w = WORKLOADS[workload]
     hq, hkv, d, B = w["hq"], w["hkv"], w["d"], w["batch"]
     sink, recent = w["sink"], w["recent"]
     n_prefill, chunk, n_decode = w["prefill"], w["chunk"], w["decode"]
@@ -260,7 +295,8 @@ def main():
     if dec_gbps:
         roof_dec = {"bound": "hbm", "achieved": round(dec_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
-                    "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("decode"),
+                    "traffic": MEASURED_TRAFFIC.get(workload, {}).get("decode"),
+                    "traffic_source": "recorded constant: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/",
                     "kernel": "duo::decode_kernel" if (group == 1 and not kv_dtype) else "duo::decode_sk_kernel",
                     "bytes_per_launch": int(avg_dec_bytes),
                     "avg_launch_us": round(dec_call_us, 2)}
@@ -268,14 +304,15 @@ def main():
     if pre_tflops:
         roof_pre = {"bound": "mfma", "achieved": round(pre_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("prefill"),
+                    "traffic": MEASURED_TRAFFIC.get(workload, {}).get("prefill"),
+                    "traffic_source": "recorded constant: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/",
                     "kernel": "duo::prefill_kernel", "flops_per_step": int(flops),
                     "avg_chunk_ms": round(pre_t * 1e3 / max(len(chunks), 1), 3)}
     dominant = roof_dec if (roof_pre is None or (roof_dec is not None and dec_t >= pre_t)) else roof_pre
 
     # ---- the oracle on the host cores, bounded sample of the same workload
     cpu = None
-    if not args.no_cpu_baseline and n_decode:
+    if with_cpu_baseline and n_decode:
         cpu = cpu_baseline(synth, args.seed, w, mask, n_prefill, B)
 
     result = {
@@ -286,7 +323,7 @@ def main():
         "higher_is_better": False if n_decode else True, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "bf16", 1: "bf16 (fp8 e4m3 KV, fp32 accumulate)",
                   2: "bf16 (int4 KV, fp32 accumulate)", 3: "bf16 (int8 KV, fp32 accumulate)"}[kv_dtype], "data": "synthetic",
-        "config": {"workload": w["desc"], "name": args.workload, "n_layers": n_layers, "n_q_heads": hq,
+        "config": {"workload": w["desc"], "name": workload, "n_layers": n_layers, "n_q_heads": hq,
                    "n_kv_heads": hkv, "head_dim": d, "retrieval_kv_heads": n_ret, "sink": sink, "recent": recent,
                    "batch": B, "prefill_tokens": n_prefill, "chunk": chunk, "decode_steps": n_decode,
                    "cache_bytes": duo.duo_cache_bytes(handle)},
@@ -298,7 +335,9 @@ def main():
         "cpu_baseline": cpu,
     }
     duo.duo_cache_destroy(handle)
-    print(json.dumps(result))
+    del keep, dec_ptrs, dec_src, chunks, out_pre, out_dec, table
+    torch.cuda.empty_cache()
+    return result
 
 
 def run_sweep(name, torch, duo, synth, lib, seed):
@@ -466,24 +505,29 @@ def cpu_baseline(synth, seed, w, mask, n_ctx, batch):
     q_heads = slice(0, hq) if whole else slice(heads[0] * group, (heads[0] + 1) * group)
     qh = synth.bf16_bits_to_f64(synth.counter_bf16(seed, 0, synth.TENSOR_Q, 0, n_ctx, n_sample, hq, d))[:, q_heads]
     sub_mask = mask[0] if whole else np.array([1], dtype=np.uint8)
-    t0 = time.perf_counter()
-    for t in range(n_sample):
-        oracle.decode_step(qh[t], kh[:n_ctx + t + 1], vh[:n_ctx + t + 1], sub_mask, sink, recent)
-    cpu_s = (time.perf_counter() - t0) / n_sample
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = 1
+
+    def timed_tokens():
+        t0 = time.perf_counter()
+        for t in range(n_sample):
+            oracle.decode_step(qh[t], kh[:n_ctx + t + 1], vh[:n_ctx + t + 1], sub_mask, sink, recent)
+        return (time.perf_counter() - t0) / n_sample
+
+    # the oracle as it stands, (a) with the numerical library's threads limited to one, (b) with all of them
+    from threadpoolctl import threadpool_info, threadpool_limits
+    with threadpool_limits(limits=1):
+        cpu_s_one = timed_tokens()
+    cpu_s = timed_tokens()
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     if whole:
-        value, what = cpu_s * batch, "%d decode tokens of sequence 0 at context %d, scaled by batch %d" % (
+        factor, what = batch, "%d decode tokens of sequence 0 at context %d, scaled by batch %d" % (
             n_sample, n_ctx, batch)
     else:
         n_groups = int(mask.sum())
-        value, what = cpu_s * n_groups * batch, ("one retrieval KV group (%d query heads) of layer 0 for one token at "
-                                                 "context %d, scaled by the %d retrieval KV groups of the %d layers"
-                                                 % (group, n_ctx, n_groups, n_layers))
-    return {"value": round(value * 1e6, 1), "unit": "us/token", "cores": int(threads), "kind": "oracle",
+        factor, what = n_groups * batch, ("one retrieval KV group (%d query heads) of layer 0 for one token at "
+                                          "context %d, scaled by the %d retrieval KV groups of the %d layers"
+                                          % (group, n_ctx, n_groups, n_layers))
+    return {"value": round(cpu_s * factor * 1e6, 1), "unit": "us/token", "cores": int(threads), "kind": "oracle",
+            "one_thread": {"value": round(cpu_s_one * factor * 1e6, 1), "unit": "us/token", "cores": 1},
             "host_cores_available": len(os.sched_getaffinity(0)),
             "sample": what + " (float64 numpy oracle; inputs regenerated on the CPU, not timed)"}
 
