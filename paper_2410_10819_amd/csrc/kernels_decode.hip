@@ -221,7 +221,10 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
   // current buffer is consumed.  Inside the loop every issue is unconditional (a
   // conditional one would make the compiler's wait counts assume the shorter queue
   // and drain it); the scheduling barriers keep the loads from being sunk below the
-  // arithmetic.  Nothing is loaded past the item's last row.
+  // arithmetic.  Nothing is loaded past the item's last row.  (Three and four buffers, with
+  // the issues running past the end of the item so that all of them stay unconditional, were
+  // measured: 0.9 and 1.3 us slower per launch at 32K context, with and without the memory-side
+  // cache - the bytes in flight are not what limits this loop.)
   if (j0 < j1) {
     int64_t base = j0;
     Buf buf_b;

@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
   // byte itself); kMid is the middle of the code range
   constexpr float kOff = INT4 ? 128.f : 0.f, kMid = INT4 ? 7.5f : 127.5f;
   constexpr int NKK = S::NKK, NMB = S::NMB, LROW = S::LROW, GROW = S::GROW;
+  constexpr int NBUF = INT4 ? 6 : 3;   // blocks of loads in flight per wavefront
   const LayerView& lv = a.lv;
   const int G = lv.group;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -553,45 +554,47 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
       }
     };
 
-    // ---- main loop: this wavefront's full blocks wave, wave + 4, ...  Three sets of raw
+    // ---- main loop: this wavefront's full blocks wave, wave + 4, ...  NBUF sets of raw
     // registers rotate: as soon as a block is staged and its K products are issued, its registers
-    // take the loads of the block three turns ahead, so up to three blocks (48 KiB of bf16 K/V)
-    // are in flight per wavefront.  In the steady loop every issue is unconditional, which lets
+    // take the loads of the block NBUF turns ahead, so up to NBUF blocks are in flight per
+    // wavefront: three of bf16 and one-byte rows (48 and 25 KiB), six of the 4-bit rows, whose
+    // blocks are a quarter of the bf16 size (six against three: 2 % faster at 3.3M tokens; four
+    // instead of three for the one-byte rows: 1 % slower).  In the steady loop every issue is unconditional, which lets
     // the compiler's wait counts match the real queue; the scheduling barriers keep the loads
     // where they are written.  Then the partly filled last block, if any, by the wavefront whose
     // turn it is.
     const int n_full = (int)((row1 - row0) / kUnit) < nb ? (int)((row1 - row0) / kUnit) : nb;
     auto run_blocks = [&](auto masked) {
-      Raw r0, r1, r2;
+      Raw rb[NBUF];
       f32x4 sacc[2];
       KeyParams kp;
       const int n_my = wave < n_full ? (n_full - wave + 3) / 4 : 0;   // blocks of this wavefront
       auto blk_of = [&](int i) { return wave + 4 * i; };
-      auto step = [&](Raw& rb, int i, bool prefetch) {
-        stage_qk(rb, sacc, kp);
+      auto step = [&](Raw& r, int i, bool prefetch) {
+        stage_qk(r, sacc, kp);
         __builtin_amdgcn_sched_barrier(0);
-        if (prefetch) issue(rb, blk_of(i + 3));
+        if (prefetch) issue(r, blk_of(i + NBUF));
         __builtin_amdgcn_sched_barrier(0);
         finish(masked, sacc, kp, row0 + (int64_t)blk_of(i) * kUnit, n_rows);
         __builtin_amdgcn_sched_barrier(0);
       };
-      if (n_my > 0) issue(r0, blk_of(0));
-      if (n_my > 1) issue(r1, blk_of(1));
-      if (n_my > 2) issue(r2, blk_of(2));
+#pragma unroll
+      for (int j = 0; j < NBUF; ++j)
+        if (n_my > j) issue(rb[j], blk_of(j));
       __builtin_amdgcn_sched_barrier(0);
       int i = 0;
-      while (i + 5 < n_my) {
-        step(r0, i, true);
-        step(r1, i + 1, true);
-        step(r2, i + 2, true);
-        i += 3;
+      while (i + 2 * NBUF - 1 < n_my) {
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j) step(rb[j], i + j, true);
+        i += NBUF;
       }
       while (i < n_my) {
-        step(r0, i, i + 3 < n_my);
-        if (i + 1 < n_my) step(r1, i + 1, i + 4 < n_my);
-        if (i + 2 < n_my) step(r2, i + 2, i + 5 < n_my);
-        i += 3;
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j)
+          if (i + j < n_my) step(rb[j], i + j, i + j + NBUF < n_my);
+        i += NBUF;
       }
+      Raw& r0 = rb[0];
       if (n_full < nb && wave == (n_full & 3)) {
         issue_tail(r0, n_full);
         stage_qk(r0, sacc, kp);
