@@ -424,10 +424,10 @@ def run_sweep(name, torch, duo, synth, lib, seed):
             h = duo.duo_cache_create(1, 1, hq, hkv, d, g_sink, g_recent, 64, np.ones((1, hkv), dtype=np.uint8))
             for n in lengths:
                 q, k, v = fill(synth.TENSOR_Q, hq, 0, n), fill(synth.TENSOR_K, hkv, 0, n), fill(synth.TENSOR_V, hkv, 0, n)
-                out, ws = torch.empty_like(q), torch.empty_like(q)
+                out = torch.empty_like(q)
                 full_pairs = hq * n * (n + 1) // 2
                 for block in (0, 128):
-                    ms = timed(lambda: duo.duo_attn_gate_mixed(h, 0, q, k, v, n, alpha, out, ws, block=block), 3)
+                    ms = timed(lambda: duo.duo_attn_gate_mixed(h, 0, q, k, v, n, alpha, out, block=block), 3)
                     if block:
                         n_sb, n_lb = -(-g_sink // block), -(-(g_recent - 1) // block) + 1
                         i = np.arange(n, dtype=np.int64)

@@ -154,10 +154,13 @@ int duo_attn_prefill_deployed(duo_cache_t* cache, int layer, const void* q, cons
  * sees key j <= i iff block j / block is among the first ceil(sink / block) blocks or fewer than
  * ceil((recent - 1) / block) + 1 blocks before block i / block (the paper shows the pattern in a
  * figure only; this is the smallest block-aligned mask of that shape containing the Lambda mask).
- * out: bf16, shape of q.  workspace: DEVICE buffer of the size of out, overwritten (it holds the
- * streaming term between the two attention launches and the mixing launch).
- * DUO_EINVAL for NULL pointers, n_tokens < 1, n_kv_heads > 64, a gate outside [0, 1] or a
- * negative block. */
+ * out: bf16, shape of q.  Two launches: full attention into out, then streaming attention whose
+ * store reads out back and writes the mixture in its place (the full term enters rounded to bf16,
+ * the streaming term and the sum in fp32, one final rounding).  workspace: not used any more, may
+ * be NULL (the argument stays for callers built against the earlier form, which needed a buffer of
+ * out's size between the launches).
+ * DUO_EINVAL for NULL q, k, v, alpha or out, n_tokens < 1, n_kv_heads > 64, a gate outside [0, 1]
+ * or a negative block. */
 int duo_attn_gate_mixed(duo_cache_t* cache, int layer, const void* q, const void* k, const void* v,
                         int n_tokens, const float* alpha, int block, void* out, void* workspace,
                         void* stream);

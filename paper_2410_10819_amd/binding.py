@@ -197,8 +197,8 @@ def duo_attn_prefill_deployed(cache, layer, q, k, v, n_new, out, lse=None, param
                                             _ptr(lse, "lse", torch.float32), _stream(stream)))
 
 
-def duo_attn_gate_mixed(cache, layer, q, k, v, n_tokens, alpha, out, workspace, block=0, stream=None):
-    """alpha: host float32 values, one per KV head; workspace: device buffer of out's size."""
+def duo_attn_gate_mixed(cache, layer, q, k, v, n_tokens, alpha, out, workspace=None, block=0, stream=None):
+    """alpha: host float32 values, one per KV head; workspace: unused (kept for the C signature), may be None."""
     import torch
     al = np.ascontiguousarray(np.asarray(alpha, dtype=np.float32))
     _check(load().duo_attn_gate_mixed(cache, layer, _ptr(q, "q", torch.bfloat16), _ptr(k, "k", torch.bfloat16),

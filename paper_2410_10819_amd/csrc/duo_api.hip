@@ -449,6 +449,7 @@ static int prefill_common(duo_cache_t* c, int layer, const void* q, const void* 
   a.lv = view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
   a.chunk_causal = chunk_causal ? 1 : 0;
   a.force_class = 0; a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
+  a.mix_with = nullptr;
   hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "prefill launch");
   return DUO_OK;
@@ -468,8 +469,8 @@ int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k,
                         const float* alpha, int block, void* out, void* workspace, void* stream) {
   int rc = check_handle_layer(c, layer);
   if (rc != DUO_OK) return rc;
-  if (!q || !k || !v || !alpha || !out || !workspace)
-    return fail(DUO_EINVAL, "q, k, v, alpha, out and workspace must not be NULL");
+  (void)workspace;   // not used any more: the mixing happens in the second launch's store
+  if (!q || !k || !v || !alpha || !out) return fail(DUO_EINVAL, "q, k, v, alpha and out must not be NULL");
   if (n_tokens < 1) return fail(DUO_EINVAL, "n_tokens must be >= 1 (got %d)", n_tokens);
   if (c->cfg.n_kv_heads > duo::kMaxGateHeads)
     return fail(DUO_EINVAL, "gate-mixed attention supports at most %d KV heads (got %d)", duo::kMaxGateHeads,
@@ -482,12 +483,14 @@ int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k,
   duo::PrefillArgs a;
   a.lv = L.view; a.q = q; a.k = k; a.v = v; a.lse = nullptr; a.pos0 = 0; a.n = n_tokens; a.chunk_causal = 0;
   a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
+  a.mix_with = nullptr;
+  for (int g = 0; g < duo::kMaxGateHeads; ++g) a.mix_alpha[g] = g < c->cfg.n_kv_heads ? alpha[g] : 0.0f;
   // full attention of every head into out
   a.out = out; a.force_class = 1;
   hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "gate-mixed full-attention launch");
-  // streaming attention of every head into the workspace
-  a.out = workspace; a.force_class = 2;
+  // streaming attention of every head, mixed with the full term on its way out (in place)
+  a.force_class = 2; a.mix_with = out;
   if (block >= 1) {
     a.win_block = block;
     a.sink_eff = (c->cfg.sink + block - 1) / block * block;
@@ -495,12 +498,6 @@ int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k,
   }
   e = duo::launch_prefill(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "gate-mixed streaming-attention launch");
-  duo::GateMixArgs m;
-  m.out = out; m.other = workspace; m.rows = (int64_t)c->cfg.batch * n_tokens;
-  m.n_q_heads = c->cfg.n_q_heads; m.group = c->cfg.n_q_heads / c->cfg.n_kv_heads; m.head_dim = c->cfg.head_dim;
-  for (int g = 0; g < duo::kMaxGateHeads; ++g) m.alpha[g] = g < c->cfg.n_kv_heads ? alpha[g] : 0.0f;
-  e = duo::launch_gate_mix(m, (hipStream_t)stream);
-  if (e != hipSuccess) return fail_hip(e, "gate-mix launch");
   return DUO_OK;
 }
 

@@ -65,6 +65,9 @@ struct DecodeArgs {
   int32_t ret_workers;  // workgroups sharing the retrieval units (0 if the layer has no retrieval head)
 };
 
+// Most KV heads a gate-mixed forward takes (their gates ride in the kernel arguments).
+constexpr int kMaxGateHeads = 64;
+
 struct PrefillArgs {
   LayerView lv;
   const void* q;       // [batch][n][n_q_heads][head_dim]
@@ -82,18 +85,13 @@ struct PrefillArgs {
   // Lambda mask (0 = the Lambda mask itself), the number of sink positions it makes visible
   // (ceil(sink / block) * block) and the number of key blocks ending at the query's own block.
   int32_t win_block, sink_eff, n_local_blocks;
+  // Gate mixing folded into the store (gate-mixed forward): when mix_with is given, the kernel writes
+  // mix_alpha[kv head] * mix_with + (1 - mix_alpha[kv head]) * (its own attention result) instead of
+  // the result itself.  mix_with has the layout of out and may be out itself (every element is read
+  // and then written by the same lane).
+  const void* mix_with;
+  float mix_alpha[kMaxGateHeads];
 };
-
-// out = alpha[kv head] * out + (1 - alpha[kv head]) * other, bf16 [rows][n_q_heads][head_dim]
-constexpr int kMaxGateHeads = 64;
-struct GateMixArgs {
-  void* out;
-  const void* other;
-  int64_t rows;          // batch * tokens
-  int32_t n_q_heads, group, head_dim;
-  float alpha[kMaxGateHeads];
-};
-hipError_t launch_gate_mix(const GateMixArgs& a, hipStream_t stream);
 
 hipError_t launch_append(const LayerView& lv, const void* k, const void* v, int64_t pos0,
                          int n_new, hipStream_t stream);

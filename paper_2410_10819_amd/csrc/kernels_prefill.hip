@@ -654,15 +654,28 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb) {
     if (ci[sb] >= a.n) continue;
-    const float inv = 1.0f / l_i[sb];
-    uint8_t* orow = (uint8_t*)a.out + (((int64_t)b * a.n + ci[sb]) * lv.n_q_heads + h) * D * 2;
+    float inv = 1.0f / l_i[sb];
+    const int64_t row_off = (((int64_t)b * a.n + ci[sb]) * lv.n_q_heads + h) * D * 2;
+    uint8_t* orow = (uint8_t*)a.out + row_off;
+    // gate-mixed forward: this launch's result enters with weight 1 - alpha, the other term (already
+    // rounded to bf16 by its own launch) with weight alpha; the sum is rounded once
+    const bool mix = a.mix_with != nullptr;
+    const float al = mix ? a.mix_alpha[kvh] : 0.f;
+    if (mix) inv *= 1.0f - al;
+    const uint8_t* xrow = (const uint8_t*)a.mix_with + row_off;
 #pragma unroll
     for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
+        float x[4] = {0.f, 0.f, 0.f, 0.f};
+        if (mix) {
+          const bf16x4 other = *(const bf16x4*)(xrow + (32 * mb + 8 * bq + 4 * half) * 2);
+#pragma unroll
+          for (int t4 = 0; t4 < 4; ++t4) x[t4] = al * (float)other[t4];
+        }
         bf16x4 w;
 #pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) w[t4] = (__bf16)(o_acc[sb][mb][4 * bq + t4] * inv);
+        for (int t4 = 0; t4 < 4; ++t4) w[t4] = (__bf16)(o_acc[sb][mb][4 * bq + t4] * inv + x[t4]);
         *(bf16x4*)(orow + (32 * mb + 8 * bq + 4 * half) * 2) = w;
       }
     if (a.lse && half == 0)
@@ -689,35 +702,7 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// out = alpha * out + (1 - alpha) * other, eight bf16 values per thread
-__global__ __launch_bounds__(256) void gate_mix_kernel(GateMixArgs a) {
-  const int64_t pieces_per_row = (int64_t)a.n_q_heads * a.head_dim / 8;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= a.rows * pieces_per_row) return;
-  const int h = (int)((idx % pieces_per_row) / (a.head_dim / 8));
-  const float al = a.alpha[h / a.group], be = 1.0f - al;
-  uint4 x = ((const uint4*)a.out)[idx];
-  const uint4 y = ((const uint4*)a.other)[idx];
-  uint32_t* xw = (uint32_t*)&x;
-  const uint32_t* yw = (const uint32_t*)&y;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float lo = al * __uint_as_float(xw[i] << 16) + be * __uint_as_float(yw[i] << 16);
-    const float hi = al * __uint_as_float(xw[i] & 0xFFFF0000u) + be * __uint_as_float(yw[i] & 0xFFFF0000u);
-    const bf16x2 pr = {(__bf16)lo, (__bf16)hi};   // round to nearest even
-    xw[i] = __builtin_bit_cast(uint32_t, pr);
-  }
-  ((uint4*)a.out)[idx] = x;
-}
-
 }  // namespace
-
-hipError_t launch_gate_mix(const GateMixArgs& a, hipStream_t stream) {
-  const int64_t n = a.rows * a.n_q_heads * a.head_dim / 8;
-  if (n <= 0) return hipSuccess;
-  gate_mix_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
-  return hipGetLastError();
-}
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   constexpr int NSB = kSubBlocks;

@@ -283,8 +283,8 @@ def test_gate_mixed_forward_at_training_length(hq, hkv, block):
     alpha[0], alpha[-1] = 1.0, 0.0
     handle = duo.duo_cache_create(1, 1, hq, hkv, d, sink, recent, 64, np.ones((1, hkv), dtype=np.uint8))
     try:
-        out, ws = torch.empty_like(q), torch.empty_like(q)
-        duo.duo_attn_gate_mixed(handle, 0, q, k, v, n, alpha, out, ws, block=block)
+        out = torch.empty_like(q)
+        duo.duo_attn_gate_mixed(handle, 0, q, k, v, n, alpha, out, block=block)
         torch.cuda.synchronize()
         got = from_dev_bits(out)[0]
     finally:

@@ -18,8 +18,7 @@ def _run(hq, hkv, d, sink, recent, batch, t, alpha, block, seed=3, check_batches
     handle = duo.duo_cache_create(1, batch, hq, hkv, d, sink, recent, 64, mask[None])
     try:
         out = torch.empty((batch, t, hq, d), dtype=torch.bfloat16, device="cuda")
-        ws = torch.empty_like(out)
-        duo.duo_attn_gate_mixed(handle, 0, to_dev(q), to_dev(k), to_dev(v), t, alpha, out, ws, block=block)
+        duo.duo_attn_gate_mixed(handle, 0, to_dev(q), to_dev(k), to_dev(v), t, alpha, out, block=block)
         torch.cuda.synchronize()
         assert duo.duo_cache_len(handle, 0) == 0
         got = from_dev_f64(out)
