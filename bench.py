@@ -32,13 +32,13 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch RECORDED from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --workload NAME`,
 # scaled by a 1 GiB device copy (summaries under profiles/): constants of the build they were taken on, not
 # measured by the run that prints them; known for these workloads only.
-MEASURED_TRAFFIC = {"c2": {"decode": 139.15e6 + 0.17e6, "prefill": 170.2e6 + 33.6e6},
-                    "c3_prefill": {"prefill": 2527.9e6 + 268.7e6},
-                    "c3_decode_b1": {"decode": 270.26e6 + 0.54e6},
-                    "c3_decode_b16": {"decode": 4308.0e6 + 0.65e6},
-                    "c4": {"decode": 2149.2e6 + 0.6e6},
-                    "c5": {"decode": 3500.7e6 + 0.56e6},
-                    "c6": {"decode": 1902.8e6 + 0.6e6}}
+MEASURED_TRAFFIC = {"c2": {"decode": 139.06e6 + 0.17e6, "prefill": 165.4e6 + 33.6e6},
+                    "c3_prefill": {"prefill": 2528.1e6 + 268.7e6},
+                    "c3_decode_b1": {"decode": 270.34e6 + 0.60e6},
+                    "c3_decode_b16": {"decode": 4307.9e6 + 0.65e6},
+                    "c4": {"decode": 2149.3e6 + 0.6e6},
+                    "c5": {"decode": 3549.4e6 + 0.6e6},
+                    "c6": {"decode": 1917.4e6 + 0.6e6}}
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
