@@ -88,3 +88,37 @@ def test_static_scratch_decode_rejects_steps_beyond_its_array():
         torch.cuda.synchronize()
     finally:
         duo.duo_cache_destroy(handle)
+
+
+@pytest.mark.parametrize("hq,hkv,kv_dtype", [(8, 8, 0), (8, 2, 1)])
+def test_static_scratch_decode_replays_from_a_graph(hq, hkv, kv_dtype):
+    # the call allocates nothing and clears its tickets with a kernel, so it can be recorded into a HIP graph:
+    # every replay, with eager work and synchronisations of the program between the replays, gives the eager bits
+    import torch
+    d, n_ctx, seed = 128, 9000, 51
+    mask = synth.retrieval_mask(seed, 1, hkv, 0.5)
+    table = device_table()
+    handle = duo.duo_cache_create(1, 2, hq, hkv, d, 16, 64, n_ctx + 1, mask, kv_dtype)
+    try:
+        fill_cache_by_append(duo, handle, table, seed, 0, 2, hkv, d, n_ctx, chunk=4096)
+        q = device_fill(table, seed, 0, synth.TENSOR_Q, 2, n_ctx, 1, hq, d)
+        k = device_fill(table, seed, 0, synth.TENSOR_K, 2, n_ctx, 1, hkv, d)
+        v = device_fill(table, seed, 0, synth.TENSOR_V, 2, n_ctx, 1, hkv, d)
+        want = torch.zeros_like(q)
+        duo.duo_attn_decode_static(handle, 0, q, want, k=k, v=v)      # eager: also the entry point's set-up on this device
+        torch.cuda.synchronize()
+        got = torch.zeros_like(q)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            duo.duo_attn_decode_static(handle, 0, q, got, k=k, v=v)
+        for i in range(4):
+            got.zero_()
+            other = torch.zeros_like(q)
+            duo.duo_attn_decode(handle, 0, q, other, k=k, v=v)         # the program's own eager work in between
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), want.view(torch.int16)), "replay %d differs from the eager call" % i
+            assert torch.equal(other.view(torch.int16), want.view(torch.int16))
+    finally:
+        duo.duo_cache_destroy(handle)
