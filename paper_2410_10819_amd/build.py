@@ -15,8 +15,12 @@ SYNTH_LIB = os.path.join(HERE, "libduosynth.so")
 
 SOURCES = ["duo_api.hip", "kernels_append.hip", "kernels_decode.hip", "kernels_decode_sk.hip", "kernels_prefill.hip"]
 SYNTH_SOURCES = ["synth_fill.hip"]
+# -amdgpu-mfma-vgpr-form: matrix-core accumulators in ordinary vector registers.  Left to itself the
+# compiler parks them in the accumulation registers once a kernel is allowed more than 256 registers
+# (the decode kernels, one workgroup per compute unit) and then copies them back and forth for every
+# vector instruction that touches them: 72-84 copies per 32-key block, a fifth of the loop's instructions.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
