@@ -75,6 +75,12 @@ def test_null_arguments_are_reported_not_dereferenced():
     assert lib.duo_kv_append(None, 0, None, None, 1, None, None) == duo.DUO_EINVAL
     assert lib.duo_attn_decode(None, 0, None, None, None, None, None, None, None) == duo.DUO_EINVAL
     assert lib.duo_attn_prefill(None, 0, None, None, None, 1, None, None, None, None) == duo.DUO_EINVAL
+    assert lib.duo_attn_prefill_deployed(None, 0, None, None, None, 1, None, None, None, None) == duo.DUO_EINVAL
+    assert lib.duo_attn_decode_static(None, 0, None, None, None, None, None, None, None) == duo.DUO_EINVAL
+    assert lib.duo_decode_step(None, 0, None, None, None, None, None, None, None) == duo.DUO_EINVAL
+    assert lib.duo_attn_gate_mixed(None, 0, None, None, None, 1, None, 0, None, None, None) == duo.DUO_EINVAL
+    assert lib.duo_set_decode_splits(None, 0) == duo.DUO_EINVAL
+    assert lib.duo_set_decode_kernel(None, 0) == duo.DUO_EINVAL
     cfg = duo.duo_config_t(**GOOD)
     cfg.retrieval_mask = None
     handle = ctypes.c_void_p()
