@@ -149,6 +149,23 @@ struct Shape {
   static constexpr int KB = MODE == 2 ? 4 : (MODE == 0 ? 16 : 8);   // bytes of K per lane, 16-key group and k-step
   static constexpr int NSC = MODE >= 2 ? 2 : 1;      // floats per row in the scale arrays
   __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
+  // Slot (16-byte unit within the LDS row) of piece `piece` of staged V row `row`.  bf16 rows: the piece
+  // index XOR an even row swizzle, which spreads the four rows one transposing read touches over the
+  // banks.  One-byte codes at D = 128 are widened by the lane that loaded them into two neighbouring
+  // pieces (2 pc, 2 pc + 1), written by two stores; with the plain layout each store of the eight lanes
+  // of a row hits every second slot, i.e. half the banks twice (36 % of this mode's LDS cycles were
+  // bank conflicts).  Here piece 2 pc + h goes to slot (pc ^ 4h) + 8h, XOR a row term: a store covers
+  // eight neighbouring slots, a read's two pieces (h = 0, 1) still differ in the bank-selecting bits,
+  // the row term's low bits separate the four rows of a read and its bit 3 alternates between
+  // neighbouring rows.  Conflict-free for 32 banks x 4 bytes and for 64.
+  __device__ static inline int v_slot(int row, int piece) {
+    if constexpr ((MODE == 1 || MODE == 3) && D == 128) {
+      const int rterm = (row & 3) | (((row ^ (row >> 2)) & 1) << 3);
+      return (piece >> 1) ^ (12 * (piece & 1)) ^ rterm;
+    } else {
+      return piece ^ v_swz(row);
+    }
+  }
   // int4: V rows are staged as codes (GROW bytes a row); 16-byte pieces swizzled so that the rows one
   // transposing read touches (keys 4 qd + r and 16 + 4 qd + r) spread over the banks
   __device__ static inline int c_swz(int row) { return (((row >> 2) & 1) * 2 + ((row >> 4) & 1)) % VPR; }
@@ -482,9 +499,9 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
         const int piece = 2 * mb + (i4 >> 1), sub8 = (i4 & 1) * 8;
         const int key_lo = 4 * qd + e, key_hi = 16 + 4 * qd + e;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            LDS_PTR(s16x4, my_v + key_lo * LROW + ((piece ^ S::v_swz(key_lo)) * 16) + sub8));
+            LDS_PTR(s16x4, my_v + key_lo * LROW + (S::v_slot(key_lo, piece) * 16) + sub8));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            LDS_PTR(s16x4, my_v + key_hi * LROW + ((piece ^ S::v_swz(key_hi)) * 16) + sub8));
+            LDS_PTR(s16x4, my_v + key_hi * LROW + (S::v_slot(key_hi, piece) * 16) + sub8));
         const bf16x8 vt = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         oacc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb, oacc[mb], 0, 0, 0);
       }
@@ -504,10 +521,10 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
         } else if constexpr (BYTES) {
           const uint2 a0 = widen4(rb.v[j].x), a1 = widen4(rb.v[j].y);
           const uint2 a2 = widen4(rb.v[j].z), a3 = widen4(rb.v[j].w);
-          *(uint4*)(my_v + row * LROW + (((2 * pc) ^ S::v_swz(row)) * 16)) = make_uint4(a0.x, a0.y, a1.x, a1.y);
-          *(uint4*)(my_v + row * LROW + (((2 * pc + 1) ^ S::v_swz(row)) * 16)) = make_uint4(a2.x, a2.y, a3.x, a3.y);
+          *(uint4*)(my_v + row * LROW + (S::v_slot(row, 2 * pc) * 16)) = make_uint4(a0.x, a0.y, a1.x, a1.y);
+          *(uint4*)(my_v + row * LROW + (S::v_slot(row, 2 * pc + 1) * 16)) = make_uint4(a2.x, a2.y, a3.x, a3.y);
         } else {
-          *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = rb.v[j];
+          *(uint4*)(my_v + row * LROW + (S::v_slot(row, pc) * 16)) = rb.v[j];
         }
       }
       bf16x8 kf[2][NKK];
@@ -736,7 +753,7 @@ __global__ __launch_bounds__(256, 1) void decode_sk_kernel(DecodeArgs a) {
 #pragma unroll
         for (int j = 0; j < kUnit * S::CPR / 64; ++j) {
           const int row = j * (64 / S::CPR) + lane / S::CPR, pc = lane % S::CPR;
-          *(uint4*)(my_v + row * LROW + ((pc ^ S::v_swz(row)) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
+          *(uint4*)(my_v + row * LROW + (S::v_slot(row, pc) * 16)) = *(const uint4*)&sm_new[1][8 * pc];
         }
       }
       KeyParams kp;

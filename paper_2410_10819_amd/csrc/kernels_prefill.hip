@@ -142,9 +142,15 @@ struct Geometry {
   static constexpr int TILE = BN * ROW;               // bytes of one K (or V) tile
   static constexpr int BUF_BYTES = 2 * TILE;          // K tile then V tile
   static constexpr int CPR = D / 8;                   // 16-byte pieces per row
-  // piece p of row r lives in slot p ^ swizzle(r)
-  __device__ static inline int k_swz(int row) { return row % CPR; }
-  __device__ static inline int v_swz(int row) { return (2 * row) % CPR; }
+  // piece p of row r lives in slot p ^ swizzle(r).  The LDS serves 256 bytes a cycle (64 banks of
+  // 4 bytes): 16 lanes of a 16-byte read, 32 lanes of an 8-byte read.  K fragments: 16 neighbouring
+  // rows read the same piece, so the swizzle takes 256 / ROW-row groups through all slots.  V^T
+  // fragments (transposing 8-byte reads): 32 lanes read four neighbouring pieces of four neighbouring
+  // rows, so the swizzle moves each row by four slots.  (Counters on an earlier layout, 2 * row for V,
+  // which is free of conflicts only for 16 lanes a cycle: a third of the LDS-active cycles of this
+  // kernel were bank conflicts.)
+  __device__ static inline int k_swz(int row) { return (row / (256 / ROW)) % CPR; }
+  __device__ static inline int v_swz(int row) { return (row * (CPR / 4)) % CPR; }
 };
 
 template <int D, int NG, int NSB>
@@ -315,11 +321,12 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
   // A tile whose 64 keys are consecutive rows of one region (the dense cache of a
   // retrieval head, or the chunk) is addressed as a wavefront-uniform base plus
   // per-lane offsets that never change; other tiles take the general path.
-  // (Successive loads of a wavefront are WPG * RPWL rows apart; the swizzle has period CPR rows,
-  // so a wavefront needs NPH sets of lane offsets, one per swizzle phase its loads fall in.)
+  // (Successive loads of a wavefront are WPG * RPWL rows apart; the swizzles repeat after SWZ_PERIOD
+  // rows, so a wavefront needs NPH sets of lane offsets, one per swizzle phase its loads fall in.)
   constexpr int XROWS = WPG * RPWL;    // rows between successive loads of one wavefront
-  constexpr int NPH = XROWS % CPR == 0 || RPWL % CPR == 0 ? 1 : CPR / XROWS;
-  static_assert(NPH == 1 || (CPR % XROWS == 0 && NLOAD % NPH == 0), "unsupported tile load geometry");
+  constexpr int SWZ_PERIOD = CPR * (256 / ROW);
+  constexpr int NPH = XROWS % SWZ_PERIOD == 0 ? 1 : SWZ_PERIOD / XROWS;
+  static_assert(NPH == 1 || (SWZ_PERIOD % XROWS == 0 && NLOAD % NPH == 0), "unsupported tile load geometry");
   int lin_k_cache[NPH], lin_v_cache[NPH], lin_k_chunk[NPH], lin_v_chunk[NPH];
 #pragma unroll
   for (int ph = 0; ph < NPH; ++ph) {
