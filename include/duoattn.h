@@ -154,11 +154,14 @@ int duo_attn_prefill_deployed(duo_cache_t* cache, int layer, const void* q, cons
  * sees key j <= i iff block j / block is among the first ceil(sink / block) blocks or fewer than
  * ceil((recent - 1) / block) + 1 blocks before block i / block (the paper shows the pattern in a
  * figure only; this is the smallest block-aligned mask of that shape containing the Lambda mask).
- * out: bf16, shape of q.  Two launches: full attention into out, then streaming attention whose
- * store reads out back and writes the mixture in its place (the full term enters rounded to bf16,
- * the streaming term and the sum in fp32, one final rounding).  workspace: not used any more, may
- * be NULL (the argument stays for callers built against the earlier form, which needed a buffer of
- * out's size between the launches).
+ * out: bf16, shape of q.  One launch and one pass over the causal keys of every head: the keys the
+ * streaming mask shows are a subset of them, so each workgroup attends to those first, stores
+ * (1 - alpha) * streaming_attn of its rows in out (rounded to bf16), carries the same online-softmax
+ * state on over the remaining keys, which turns it into the full-attention state, and writes
+ * alpha * full_attn + (the stored term), computed in fp32 and rounded once.  Rows whose causal keys
+ * are all inside the streaming mask get the common value of both terms.  workspace: not used, may
+ * be NULL (the argument stays for callers built against an earlier form, which needed a buffer of
+ * out's size).
  * DUO_EINVAL for NULL q, k, v, alpha or out, n_tokens < 1, n_kv_heads > 64, a gate outside [0, 1]
  * or a negative block. */
 int duo_attn_gate_mixed(duo_cache_t* cache, int layer, const void* q, const void* k, const void* v,

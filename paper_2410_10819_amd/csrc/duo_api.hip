@@ -448,8 +448,7 @@ static int prefill_common(duo_cache_t* c, int layer, const void* q, const void* 
   duo::PrefillArgs a;
   a.lv = view; a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.pos0 = L.len; a.n = n_new;
   a.chunk_causal = chunk_causal ? 1 : 0;
-  a.force_class = 0; a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
-  a.mix_with = nullptr;
+  a.dual = 0; a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
   hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "prefill launch");
   return DUO_OK;
@@ -469,7 +468,7 @@ int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k,
                         const float* alpha, int block, void* out, void* workspace, void* stream) {
   int rc = check_handle_layer(c, layer);
   if (rc != DUO_OK) return rc;
-  (void)workspace;   // not used any more: the mixing happens in the second launch's store
+  (void)workspace;   // not used: both terms come from one pass and are mixed in registers and in out
   if (!q || !k || !v || !alpha || !out) return fail(DUO_EINVAL, "q, k, v, alpha and out must not be NULL");
   if (n_tokens < 1) return fail(DUO_EINVAL, "n_tokens must be >= 1 (got %d)", n_tokens);
   if (c->cfg.n_kv_heads > duo::kMaxGateHeads)
@@ -483,21 +482,15 @@ int duo_attn_gate_mixed(duo_cache_t* c, int layer, const void* q, const void* k,
   duo::PrefillArgs a;
   a.lv = L.view; a.q = q; a.k = k; a.v = v; a.lse = nullptr; a.pos0 = 0; a.n = n_tokens; a.chunk_causal = 0;
   a.win_block = 0; a.sink_eff = 0; a.n_local_blocks = 0;
-  a.mix_with = nullptr;
   for (int g = 0; g < duo::kMaxGateHeads; ++g) a.mix_alpha[g] = g < c->cfg.n_kv_heads ? alpha[g] : 0.0f;
-  // full attention of every head into out
-  a.out = out; a.force_class = 1;
-  hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
-  if (e != hipSuccess) return fail_hip(e, "gate-mixed full-attention launch");
-  // streaming attention of every head, mixed with the full term on its way out (in place)
-  a.force_class = 2; a.mix_with = out;
+  a.out = out; a.dual = 1;
   if (block >= 1) {
     a.win_block = block;
     a.sink_eff = (c->cfg.sink + block - 1) / block * block;
     a.n_local_blocks = (c->cfg.recent - 1 + block - 1) / block + 1;
   }
-  e = duo::launch_prefill(a, (hipStream_t)stream);
-  if (e != hipSuccess) return fail_hip(e, "gate-mixed streaming-attention launch");
+  hipError_t e = duo::launch_prefill(a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "gate-mixed attention launch");
   return DUO_OK;
 }
 

@@ -78,18 +78,18 @@ struct PrefillArgs {
   int64_t pos0;        // tokens in the cache = position of the chunk's first query
   int32_t n;           // chunk length
   int32_t chunk_causal;  // streaming heads: causal attention over [retained cache || chunk] instead of the Lambda mask
-  // Whole-sequence forward without a cache (pos0 = 0): treat every head as a retrieval head (1) or
-  // as a streaming head (2) whatever the layer's classes are; 0 = use the layer's classes.
-  int32_t force_class;
-  // Streaming heads with force_class = 2: block size of the block-aligned approximation of the
-  // Lambda mask (0 = the Lambda mask itself), the number of sink positions it makes visible
+  // Gate-mixed forward (whole sequence, no cache, pos0 = 0): every head is attended to twice from one
+  // pass over its causal keys.  The keys the streaming mask shows (sinks and window) are a subset of
+  // the causal ones, so a workgroup runs them first, writes the streaming term scaled by
+  // 1 - mix_alpha[kv head] to out, continues the SAME online-softmax state over the remaining
+  // ("middle") keys, which makes it the full-attention state, and finally writes
+  // mix_alpha * full + (what it stored before).  Every score is computed once, except in the few
+  // tiles that hold both kinds of keys.
+  int32_t dual;
+  // Streaming mask of the dual pass: block size of the block-aligned approximation of the Lambda
+  // mask (0 = the Lambda mask itself), the number of sink positions it makes visible
   // (ceil(sink / block) * block) and the number of key blocks ending at the query's own block.
   int32_t win_block, sink_eff, n_local_blocks;
-  // Gate mixing folded into the store (gate-mixed forward): when mix_with is given, the kernel writes
-  // mix_alpha[kv head] * mix_with + (1 - mix_alpha[kv head]) * (its own attention result) instead of
-  // the result itself.  mix_with has the layout of out and may be out itself (every element is read
-  // and then written by the same lane).
-  const void* mix_with;
   float mix_alpha[kMaxGateHeads];
 };
 

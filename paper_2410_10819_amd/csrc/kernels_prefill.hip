@@ -153,8 +153,11 @@ struct Geometry {
   __device__ static inline int v_swz(int row) { return (row * (CPR / 4)) % CPR; }
 };
 
-template <int D, int NG, int NSB>
+// DUAL: the gate-mixed forward's pass (PrefillArgs::dual), an instantiation of its own so that the
+// chunked pre-filling loop carries none of its bookkeeping.
+template <int D, int NG, int NSB, bool DUAL>
 __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kernel(PrefillArgs a) {
+  static_assert(!DUAL || NG == 1, "the dual pass hands one running state from its streaming part to its middle part");
   using Geo = Geometry<D>;
   constexpr int ROW = Geo::ROW, TILE = Geo::TILE, BUF_BYTES = Geo::BUF_BYTES;
   constexpr int NKK = D / 16;          // MFMA k-steps of the QK^T contraction
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
     const int rb_per_bundle = kBundle / lv.group;
     const int bundles_per_head = (n_rb + rb_per_bundle - 1) / rb_per_bundle;
     if (rank >= lv.n_kv_heads * bundles_per_head) return;
-    const int n_heavy = a.force_class == 1 ? lv.n_kv_heads : (a.force_class == 2 ? 0 : lv.n_ret);
+    const int n_heavy = DUAL ? lv.n_kv_heads : lv.n_ret;   // the dual pass is causal for every head
     int kv_slot, c;
     if (rank < n_heavy * bundles_per_head) {
       c = rank / n_heavy; kv_slot = rank % n_heavy;
@@ -211,7 +214,9 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
   const int slot_head = (int)(info & ~kRetrievalBit);
 
   KeySource ks;
-  ks.retrieval = a.force_class ? a.force_class == 1 : (info & kRetrievalBit) != 0;
+  constexpr bool dual = DUAL;
+  // the dual pass reads no cache (pos0 = 0): its key list is that of a retrieval head, the chunk's positions
+  ks.retrieval = dual || (info & kRetrievalBit) != 0;
   // sink positions of the streaming list; the block-aligned mask widens them to whole blocks
   const int sink_k = a.win_block ? a.sink_eff : lv.sink;
   ks.pos0 = a.pos0;
@@ -254,7 +259,8 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
   // A list that is attended causally as a whole: every retrieval head, and a streaming head in
   // the deployed chunk-causal mode (causal attention over [retained cache || chunk]).  The list
   // entry of a chunk position p is p - gap.
-  const bool causal_list = ks.retrieval || a.chunk_causal != 0;
+  // The dual pass orders and masks its tiles itself: streaming part under the Lambda mask first.
+  const bool causal_list = !dual && (ks.retrieval || a.chunk_causal != 0);
   const int64_t gap = ks.tail_pos - ks.n_head;
   // Tile list of the workgroup: [0, tA_end) covers the sink part, [tB_begin, t_end) the window.
   int64_t tA_end, tB_begin, t_end;
@@ -274,11 +280,23 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
     t_end = u_hi / BN + 1;
     if (t_end < tA_end) t_end = tA_end;
   }
-  const int n_tiles = (int)(tA_end + (t_end - tB_begin));
+  // Dual pass: after the n_lambda tiles of the streaming part come the tiles [tM_begin, tM_end) that hold
+  // "middle" keys - causal, but neither sink nor in the window - of some row of the workgroup: positions
+  // sink .. (first window position of the last row) - 1.  Tiles that hold keys of both kinds are visited
+  // in both parts, with complementary masks.
+  const int n_lambda = (int)(tA_end + (t_end - tB_begin));
+  int64_t tM_begin = 0, tM_end = 0;
+  if (dual) {
+    int64_t wfirst = a.win_block ? (qpos_last / a.win_block - a.n_local_blocks + 1) * (int64_t)a.win_block
+                                 : qpos_last - lv.recent + 1;
+    if (wfirst > (int64_t)sink_k) { tM_begin = sink_k / BN; tM_end = (wfirst - 1) / BN + 1; }
+  }
+  const int n_middle = (int)(tM_end - tM_begin);
+  const int n_tiles = n_lambda + n_middle;
   const int n_iter = (n_tiles + NG - 1) / NG;
   // Tile indices fit 32 bits; the per-iteration bookkeeping below is 32-bit scalar arithmetic.
-  const int tA = (int)tA_end, tB = (int)tB_begin;
-  auto tile_of = [&](int s) -> int { return s < tA ? s : tB + (s - tA); };
+  const int tA = (int)tA_end, tB = (int)tB_begin, tM = (int)tM_begin;
+  auto tile_of = [&](int s) -> int { return s < tA ? s : (s < n_lambda ? tB + (s - tA) : tM + (s - n_lambda)); };
   // Classes of tiles, by index: [0, t_dense_end) lie wholly in the dense cache of a retrieval head;
   // [t_chunk_begin, t_whole_end) lie wholly in the chunk; tiles from t_whole_end on are cut by
   // the end of the list; the others straddle regions and take the general load path.
@@ -465,13 +483,23 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
     }
   };
 
+  // Dual pass: first window position of the wavefront's first row, per sub-block.
+  int64_t mid_w0[NSB];
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb) {
+    const int64_t q0 = a.pos0 + (row_w + 32 * sb < a.n ? row_w + 32 * sb : a.n - 1);
+    mid_w0[sb] = !dual ? 0 : (a.win_block ? (q0 / a.win_block - a.n_local_blocks + 1) * (int64_t)a.win_block : q0 - lv.recent + 1);
+  }
   // Online softmax of the tile whose first key is list entry ub: s_acc -> pf, m_i, l_i; rescales o_acc.
-  auto softmax_phase = [&](int t) {
+  auto softmax_phase = [&](int t, bool middle) {
     const int64_t ub = (int64_t)t * BN;
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
-      // Mask (only tiles that touch the mask boundary or the end of the list).
-      const bool need_mask = !causal_list || t >= t_mask[sb];
+      // Mask (only tiles that touch the mask boundary or the end of the list).  A tile of the middle
+      // part needs none if it starts after the sinks and ends before the window of the wavefront's
+      // first row of this sub-block (window starts never decrease with the query).
+      bool need_mask = !causal_list || t >= t_mask[sb];
+      if (middle) need_mask = !(ub >= (int64_t)sink_k && ub + BN - 1 < mid_w0[sb]);
       // Online softmax for this lane's query column; `score(kb, r)` yields the masked score.
       auto softmax_block = [&](auto&& score) {
         float mx = -INFINITY;
@@ -554,18 +582,52 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
           int w_hi = lim - 1 < qb ? lim - 1 : qb;
           int w_lo = qb - win + 1;
           if (gap32 > 0 && w_lo < nh_rel) w_lo = nh_rel;
-          s_hi -= 4 * half; w_hi -= 4 * half; w_lo -= 4 * half;
+          if (middle) {
+            // the complement within the causal keys: from the first position after the sinks up to
+            // the one before the query's window (there is no gap in the dual pass's list)
+            const int m_lo = sink_rel - 4 * half, m_hi = w_lo - 1 - 4 * half;
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int c = 32 * kb + 8 * (r / 4) + (r % 4);
-              const bool vis = (c <= s_hi) | ((c >= w_lo) & (c <= w_hi));
-              if (!vis) sv[kb][r] = -INFINITY;
-            }
+              for (int r = 0; r < 16; ++r) {
+                const int c = 32 * kb + 8 * (r / 4) + (r % 4);
+                if (!((c >= m_lo) & (c <= m_hi))) sv[kb][r] = -INFINITY;
+              }
+          } else {
+            s_hi -= 4 * half; w_hi -= 4 * half; w_lo -= 4 * half;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int c = 32 * kb + 8 * (r / 4) + (r % 4);
+                const bool vis = (c <= s_hi) | ((c >= w_lo) & (c <= w_hi));
+                if (!vis) sv[kb][r] = -INFINITY;
+              }
+          }
         }
         softmax_block([&](int kb, int r) { return sv[kb][r]; });
       }
+    }
+  };
+
+  // Dual pass, between its two parts: (1 - alpha) * (streaming attention of the wavefront's rows) -> out.
+  // The final store reads it back (the same lane, the same addresses) and adds alpha * full attention.
+  auto emit_streaming_term = [&]() {
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb) {
+      if (ci[sb] >= a.n) continue;
+      const HalfPair hp = both_halves(l_i[sb]);
+      const float inv = (1.0f - a.mix_alpha[kvh]) / (hp.a + hp.b);
+      uint8_t* orow = (uint8_t*)a.out + (((int64_t)b * a.n + ci[sb]) * lv.n_q_heads + h) * D * 2;
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq) {
+          bf16x4 w;
+#pragma unroll
+          for (int t4 = 0; t4 < 4; ++t4) w[t4] = (__bf16)(o_acc[sb][mb][4 * bq + t4] * inv);
+          *(bf16x4*)(orow + (32 * mb + 8 * bq + 4 * half) * 2) = w;
+        }
     }
   };
 
@@ -600,13 +662,15 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
       issue_l(it + 1);
       m_phase(vbuf(it - 1), kbuf(it), live_pv, live_qk);
       __builtin_amdgcn_sched_barrier(0);
+      // dual pass: O, m, l now cover exactly the streaming part (its last tile's P V has just been added)
+      if (NG == 1 && dual && n_middle > 0 && it == n_lambda) emit_streaming_term();
       // the iteration's one barrier: after the matrix-core block for the wavefronts that run the
       // softmax first, after the softmax for the others
       if (s_first) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __builtin_amdgcn_s_barrier();
       }
-      if (live_qk) softmax_phase(tile_of(s));
+      if (live_qk) softmax_phase(tile_of(s), dual && s >= n_lambda);
       __builtin_amdgcn_sched_barrier(0);
       if (!s_first) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -664,21 +728,20 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
     float inv = 1.0f / l_i[sb];
     const int64_t row_off = (((int64_t)b * a.n + ci[sb]) * lv.n_q_heads + h) * D * 2;
     uint8_t* orow = (uint8_t*)a.out + row_off;
-    // gate-mixed forward: this launch's result enters with weight 1 - alpha, the other term (already
-    // rounded to bf16 by its own launch) with weight alpha; the sum is rounded once
-    const bool mix = a.mix_with != nullptr;
-    const float al = mix ? a.mix_alpha[kvh] : 0.f;
-    if (mix) inv *= 1.0f - al;
-    const uint8_t* xrow = (const uint8_t*)a.mix_with + row_off;
+    // dual pass with a middle part: the state is now full attention, which enters with weight alpha
+    // beside the streaming term stored earlier (already rounded to bf16 once); the sum is rounded once.
+    // Without a middle part the two terms are the same and the result is written as it is.
+    const bool mix = NG == 1 && dual && n_middle > 0;
+    if (mix) inv *= a.mix_alpha[kvh];
 #pragma unroll
     for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
         float x[4] = {0.f, 0.f, 0.f, 0.f};
         if (mix) {
-          const bf16x4 other = *(const bf16x4*)(xrow + (32 * mb + 8 * bq + 4 * half) * 2);
+          const bf16x4 other = *(const bf16x4*)(orow + (32 * mb + 8 * bq + 4 * half) * 2);
 #pragma unroll
-          for (int t4 = 0; t4 < 4; ++t4) x[t4] = al * (float)other[t4];
+          for (int t4 = 0; t4 < 4; ++t4) x[t4] = (float)other[t4];
         }
         bf16x4 w;
 #pragma unroll
@@ -690,14 +753,14 @@ __global__ __launch_bounds__(NSB == 2 ? 256 : kWaves * 64, 1) void prefill_kerne
   }
 }
 
-template <int D, int NG, int NSB>
+template <int D, int NG, int NSB, bool DUAL>
 hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
   constexpr int NW = NSB == 2 ? 4 : kWaves;
   constexpr int BM = 32 * NSB * (NW / NG);
   constexpr int lds = NG * 2 * Geometry<D>::BUF_BYTES;
   static bool configured = false;   // one attribute call per kernel instantiation and process
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<D, NG, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<D, NG, NSB, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -705,7 +768,7 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
   const int rb_per_bundle = kBundle / a.lv.group;
   const int bundles = a.lv.n_kv_heads * ((n_rb + rb_per_bundle - 1) / rb_per_bundle);
   dim3 grid((unsigned)((bundles + kDies - 1) / kDies * kDies * kBundle), a.lv.batch);
-  prefill_kernel<D, NG, NSB><<<grid, NW * 64, lds, stream>>>(a);
+  prefill_kernel<D, NG, NSB, DUAL><<<grid, NW * 64, lds, stream>>>(a);
   return hipGetLastError();
 }
 
@@ -714,11 +777,13 @@ hipError_t launch_one(const PrefillArgs& a, hipStream_t stream) {
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   constexpr int NSB = kSubBlocks;
   // Two key groups per workgroup when 256-row blocks alone would leave compute units idle.
-  const int n_heavy_heads = a.force_class == 1 ? a.lv.n_kv_heads : (a.force_class == 2 ? 0 : a.lv.n_ret);
+  // (The dual pass hands one running state from its streaming part to its middle part and so keeps one key group.)
+  const int n_heavy_heads = a.dual ? a.lv.n_kv_heads : a.lv.n_ret;
   const int64_t heavy_blocks = (int64_t)a.lv.batch * n_heavy_heads * a.lv.group * ((a.n + 255) / 256);
+  if (a.dual) return a.lv.head_dim == 128 ? launch_one<128, 1, NSB, true>(a, stream) : launch_one<64, 1, NSB, true>(a, stream);
   const bool split_keys = heavy_blocks < 384;
-  if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB>(a, stream) : launch_one<128, 1, NSB>(a, stream);
-  return split_keys ? launch_one<64, 2, NSB>(a, stream) : launch_one<64, 1, NSB>(a, stream);
+  if (a.lv.head_dim == 128) return split_keys ? launch_one<128, 2, NSB, false>(a, stream) : launch_one<128, 1, NSB, false>(a, stream);
+  return split_keys ? launch_one<64, 2, NSB, false>(a, stream) : launch_one<64, 1, NSB, false>(a, stream);
 }
 
 }  // namespace duo
